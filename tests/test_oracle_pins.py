@@ -1,0 +1,433 @@
+"""Pins for the CPU oracle: everything it computes is checked against something
+other than itself — published known-answer vectors, numpy library routines,
+pure-Python brute force from the raw event list, closed-form probabilities.
+No GPU needed."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+from scipy import stats
+
+import oracle
+
+MASK64 = (1 << 64) - 1
+
+
+# --------------------------------------------------------------------------- RNG
+def test_philox_known_answers(golden_dir):
+    """Published known-answer vectors of Philox4x32-10 (Salmon et al., SC'11)."""
+    rows = [l.split() for l in open(os.path.join(golden_dir, "philox4x32_10_kat.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        v = [int(x, 16) for x in r]
+        out = oracle.philox4x32_10(v[0:4], v[4:6])
+        assert [int(x) for x in out] == v[6:10]
+
+
+def test_draw64_counter_layout():
+    """key = seed halves, counter = (root lo, root hi, slot, hop), result = word1:word0."""
+    for seed, hop, root, slot in [(42, 0, 0, 0), (0xDEADBEEFCAFEF00D, 1, (1 << 33) + 7, 9),
+                                  (1, 3, 599999, 31)]:
+        out = oracle.philox4x32_10([root & 0xFFFFFFFF, root >> 32, slot, hop],
+                                   [seed & 0xFFFFFFFF, seed >> 32])
+        assert oracle.draw64(seed, hop, root, slot) == (int(out[1]) << 32) | int(out[0])
+
+
+def test_mulhi64_against_bigints():
+    rng = np.random.default_rng(0)
+    cases = [(0, 5), (MASK64, 1), (MASK64, MASK64), (1 << 63, 3), (12345, 0)]
+    cases += [(int(a), int(b)) for a, b in rng.integers(0, 1 << 63, (200, 2), dtype=np.uint64)]
+    cases += [(int(a) * 2 + 1, int(b)) for a, b in rng.integers(0, 1 << 63, (200, 2), dtype=np.uint64)]
+    for u, n in cases:
+        assert oracle.mulhi64(u, n) == (u * n) >> 64
+
+
+def test_draw64_bits_equidistributed():
+    """Low and high bytes of the draws are uniform (chi-square, fixed seed)."""
+    d = np.array([oracle.draw64(7, 0, r, 0) for r in range(40000)], dtype=np.uint64)
+    for shift in (0, 24, 56):
+        obs = np.bincount(((d >> np.uint64(shift)) & np.uint64(255)).astype(np.int64), minlength=256)
+        chi = ((obs - 40000 / 256) ** 2 / (40000 / 256)).sum()
+        assert chi < stats.chi2.ppf(1 - 1e-4, 255)
+
+
+# --------------------------------------------------------------------------- T-CSR
+def _random_events(rng, n_nodes, n, t_span, sorted_ts):
+    src = rng.integers(0, n_nodes, n).astype(np.int32)
+    dst = rng.integers(0, n_nodes, n).astype(np.int32)
+    ts = rng.integers(0, t_span, n).astype(np.int64)
+    if sorted_ts:
+        ts.sort()
+    eid = rng.permutation(n).astype(np.int32)
+    return src, dst, ts, eid
+
+
+@pytest.mark.parametrize("sorted_ts", [True, False])
+@pytest.mark.parametrize("threads", [1, 4])
+def test_tcsr_equals_lexsort(sorted_ts, threads):
+    """Per-node lists sorted by timestamp (Sec. 3.3), ties by input position:
+    the same thing as numpy.lexsort with keys (src, ts, position)."""
+    rng = np.random.default_rng(11)
+    n_nodes, n = 37, 5000
+    src, dst, ts, eid = _random_events(rng, n_nodes, n, 300, sorted_ts)   # heavy ties
+    src[src == 5] = 6                                                     # an empty node
+    indptr, o_nbr, o_ts, o_eid = oracle.tcsr_build(src, dst, ts, eid, n_nodes, threads)
+    perm = np.lexsort((np.arange(n), ts, src))
+    assert np.array_equal(o_nbr, dst[perm])
+    assert np.array_equal(o_ts, ts[perm])
+    assert np.array_equal(o_eid, eid[perm])
+    assert np.array_equal(indptr, np.concatenate([[0], np.cumsum(np.bincount(src, minlength=n_nodes))]))
+    assert indptr[5] == indptr[6] and indptr[-1] == n
+    for v in range(n_nodes):
+        seg = o_ts[indptr[v]:indptr[v + 1]]
+        assert np.all(np.diff(seg) >= 0)
+        got = sorted(zip(o_nbr[indptr[v]:indptr[v + 1]], seg, o_eid[indptr[v]:indptr[v + 1]]))
+        want = sorted(zip(dst[src == v], ts[src == v], eid[src == v]))
+        assert got == want
+
+
+def test_tcsr_rejects_bad_node():
+    with pytest.raises(ValueError):
+        oracle.tcsr_build([0, 3], [1, 1], [0, 1], [0, 1], 3)
+
+
+# --------------------------------------------------------------------------- cutoff + most recent
+def _brute_force_neighborhood(src, dst, ts, eid, v, t):
+    """N(v,t) = {(u,t_u) : (v,u,t_u) in E, t_u < t} (Sec. 2.1) straight from the raw
+    event list, latest first, ties by later input position first."""
+    cand = [(int(ts[i]), i) for i in range(len(src)) if src[i] == v and ts[i] < t]
+    cand.sort(reverse=True)
+    return [(int(dst[i]), int(eid[i]), tt) for tt, i in cand]
+
+
+def _check_padding(o, q, c, k):
+    assert o["count"][q] == c
+    assert np.all(o["nbr"][q, c:] == -1) and np.all(o["eid"][q, c:] == -1) and np.all(o["ts"][q, c:] == 0)
+
+
+@pytest.mark.parametrize("sorted_ts", [True, False])
+def test_most_recent_equals_brute_force(sorted_ts):
+    rng = np.random.default_rng(5)
+    n_nodes, n, k = 12, 600, 7
+    src, dst, ts, eid = _random_events(rng, n_nodes, n, 80, sorted_ts)
+    src[src == 3] = 4
+    g = oracle.tcsr_build(src, dst, ts, eid, n_nodes)
+    roots = rng.integers(0, n_nodes, 300).astype(np.int32)
+    times = rng.integers(-2, 85, 300).astype(np.int64)
+    o = oracle.sample_temporal(g, roots, times, k, 1, oracle.RECENT, seed=1)[0]
+    for q in range(300):
+        want = _brute_force_neighborhood(src, dst, ts, eid, roots[q], times[q])[:k]
+        c = len(want)
+        _check_padding(o, q, c, k)
+        got = list(zip(o["nbr"][q, :c].tolist(), o["eid"][q, :c].tolist(), o["ts"][q, :c].tolist()))
+        assert got == want
+
+
+def test_cutoff_equals_searchsorted_and_edge_cases():
+    """count (with k above every degree) is numpy.searchsorted(side='left') on the
+    node's time-sorted list: strict '<' (Sec. 2.1)."""
+    rng = np.random.default_rng(9)
+    n_nodes, n = 9, 2000
+    src, dst, ts, eid = _random_events(rng, n_nodes, n, 50, True)
+    src[src == 2] = 1
+    ts[src == 7] = 20                                  # a node whose timestamps are all equal
+    g = oracle.tcsr_build(src, dst, ts, eid, n_nodes)
+    indptr, _, gts, _ = g
+    k = int(np.diff(indptr).max()) + 1
+    roots = np.repeat(np.arange(n_nodes, dtype=np.int32), 56)
+    times = np.tile(np.arange(-3, 53, dtype=np.int64), n_nodes)
+    o = oracle.sample_temporal(g, roots, times, k, 1, oracle.RECENT, seed=0)[0]
+    for q in range(roots.shape[0]):
+        seg = gts[indptr[roots[q]]:indptr[roots[q] + 1]]
+        assert o["count"][q] == np.searchsorted(seg, times[q], side="left")
+        assert np.all(o["ts"][q, :o["count"][q]] < times[q])
+    sel = roots == 2
+    assert np.all(o["count"][sel] == 0)                # empty list
+    sel7 = roots == 7
+    deg7 = indptr[8] - indptr[7]
+    assert np.all(o["count"][sel7 & (times <= 20)] == 0)      # a tie with t is excluded
+    assert np.all(o["count"][sel7 & (times > 20)] == deg7)
+
+
+def test_most_recent_invariant_under_root_order():
+    """Arbitrary (non-chronological) root order must work (Sec. 1, 4.3)."""
+    rng = np.random.default_rng(2)
+    src, dst, ts, eid = _random_events(rng, 20, 1500, 1000, True)
+    g = oracle.tcsr_build(src, dst, ts, eid, 20)
+    roots = rng.integers(0, 20, 200).astype(np.int32)
+    times = rng.integers(0, 1000, 200).astype(np.int64)
+    a = oracle.sample_temporal(g, roots, times, 5, 1, oracle.RECENT, seed=0)[0]
+    p = rng.permutation(200)
+    b = oracle.sample_temporal(g, roots[p], times[p], 5, 1, oracle.RECENT, seed=0)[0]
+    for name in ("nbr", "eid", "ts", "count"):
+        assert np.array_equal(a[name][p], b[name])
+
+
+# --------------------------------------------------------------------------- uniform
+def _single_node_graph(cnt, extra_after=3):
+    """One node (id 0) with `cnt` entries before t = 10**6 and a few after it.
+    Entry p has neighbor id p, edge id 1000 + p, timestamp 10 * p."""
+    n = cnt + extra_after
+    src = np.zeros(n, np.int32)
+    dst = np.arange(n, dtype=np.int32)
+    ts = np.arange(n, dtype=np.int64) * 10
+    ts[cnt:] += 10 ** 6
+    eid = (1000 + np.arange(n)).astype(np.int32)
+    return oracle.tcsr_build(src, dst, ts, eid, 1), 10 ** 6
+
+
+def _fisher_yates_positions(seed, hop, q, cnt, k):
+    """Partial Fisher-Yates on an explicit array, Python integers only."""
+    a = list(range(cnt))
+    out = []
+    for j in range(k):
+        r = j + ((oracle.draw64(seed, hop, q, j) * (cnt - j)) >> 64)
+        a[j], a[r] = a[r], a[j]
+        out.append(a[j])
+    return out
+
+
+@pytest.mark.parametrize("cnt,k", [(11, 10), (12, 3), (64, 10), (1000, 10), (33, 32)])
+def test_uniform_equals_explicit_fisher_yates(cnt, k):
+    g, t = _single_node_graph(cnt)
+    R = 400
+    o = oracle.sample_hop(g, np.zeros(R, np.int32), np.full(R, t, np.int64), k, oracle.UNIFORM,
+                          seed=99, hop=1)
+    for q in range(R):
+        pos = _fisher_yates_positions(99, 1, q, cnt, k)
+        assert o["nbr"][q].tolist() == pos                      # neighbor id == position
+        assert o["eid"][q].tolist() == [1000 + p for p in pos]
+        assert o["ts"][q].tolist() == [10 * p for p in pos]
+        assert len(set(pos)) == k and max(pos) < cnt            # distinct, strictly before t
+        assert o["count"][q] == k
+
+
+def test_uniform_small_neighborhood_returns_all_most_recent_first():
+    for cnt in (0, 1, 4, 10):
+        g, t = _single_node_graph(cnt)
+        u = oracle.sample_hop(g, np.zeros(5, np.int32), np.full(5, t, np.int64), 10, oracle.UNIFORM, 3, 0)
+        r = oracle.sample_hop(g, np.zeros(5, np.int32), np.full(5, t, np.int64), 10, oracle.RECENT, 3, 0)
+        for name in ("nbr", "eid", "ts", "count"):
+            assert np.array_equal(u[name], r[name])
+        assert np.all(u["count"] == cnt)
+
+
+def test_uniform_ordered_pairs_equiprobable():
+    """cnt = 5, k = 2: the 20 ordered pairs are equiprobable (exact multinomial)."""
+    g, t = _single_node_graph(5)
+    R = 100000
+    o = oracle.sample_hop(g, np.zeros(R, np.int32), np.full(R, t, np.int64), 2, oracle.UNIFORM, 2024, 0,
+                          threads=4)
+    code = o["nbr"][:, 0] * 5 + o["nbr"][:, 1]
+    obs = np.bincount(code, minlength=25)
+    pairs = [a * 5 + b for a in range(5) for b in range(5) if a != b]
+    assert obs.sum() == obs[pairs].sum()
+    chi = ((obs[pairs] - R / 20) ** 2 / (R / 20)).sum()
+    assert chi < stats.chi2.ppf(1 - 1e-4, 19)
+
+
+@pytest.mark.parametrize("cnt", [11, 64, 1000])
+def test_uniform_slot_marginals(cnt):
+    """Each slot's marginal is uniform over the cnt valid positions."""
+    g, t = _single_node_graph(cnt)
+    R = 60000
+    o = oracle.sample_hop(g, np.zeros(R, np.int32), np.full(R, t, np.int64), 10, oracle.UNIFORM, 5, 1,
+                          threads=4)
+    for slot in (0, 4, 9):
+        obs = np.bincount(o["nbr"][:, slot], minlength=cnt)
+        assert obs.shape[0] == cnt
+        chi = ((obs - R / cnt) ** 2 / (R / cnt)).sum()
+        assert chi < stats.chi2.ppf(1 - 1e-4, cnt - 1)
+
+
+# --------------------------------------------------------------------------- weighted
+def _weighted_graph(weights_recent_first, extra_older=0):
+    """One node whose candidate i (most recent first) carries weights_recent_first[i]."""
+    c = len(weights_recent_first)
+    cnt = c + extra_older
+    g, t = _single_node_graph(cnt)
+    ew = np.ones(1000 + cnt + 3, np.uint32)
+    for i, w in enumerate(weights_recent_first):
+        ew[1000 + (cnt - 1 - i)] = w                    # candidate i = entry cnt-1-i
+    return g, t, ew, cnt
+
+
+def _successive_probs(w, k):
+    """Closed form for successive sampling without replacement:
+    P(i1,..,ik) = prod_j w_ij / (W - sum of earlier picks)."""
+    out = {}
+    for seq in itertools.permutations(range(len(w)), k):
+        p, rest = 1.0, float(sum(w))
+        for i in seq:
+            p *= w[i] / rest
+            rest -= w[i]
+        out[seq] = p
+    return out
+
+
+def test_weighted_equals_stepwise_python():
+    w = [5, 1, 9, 2, 2, 7, 1, 30, 4, 4, 6, 3]
+    g, t, ew, cnt = _weighted_graph(w, extra_older=20)
+    R, k, m = 300, 4, len(w)
+    o = oracle.sample_hop(g, np.zeros(R, np.int32), np.full(R, t, np.int64), k, oracle.WEIGHTED, 8, 1,
+                          m=m, edge_weight=ew)
+    for q in range(R):
+        rem = list(w)
+        for j in range(k):
+            x = (oracle.draw64(8, 1, q, j) * sum(rem)) >> 64
+            acc, pick = 0, None
+            for i, wi in enumerate(rem):
+                acc += wi
+                if acc > x:
+                    pick = i
+                    break
+            rem[pick] = 0
+            assert o["nbr"][q, j] == cnt - 1 - pick      # neighbor id == entry position
+        assert o["count"][q] == k
+
+
+def test_weighted_ordered_pairs_closed_form():
+    w = [1, 2, 3, 4, 10]
+    g, t, ew, cnt = _weighted_graph(w)
+    R = 120000
+    o = oracle.sample_hop(g, np.zeros(R, np.int32), np.full(R, t, np.int64), 2, oracle.WEIGHTED, 77, 0,
+                          m=5, edge_weight=ew, threads=4)
+    cand = cnt - 1 - o["nbr"]                            # back to candidate indices
+    probs = _successive_probs(w, 2)
+    obs = np.array([np.sum((cand[:, 0] == a) & (cand[:, 1] == b)) for (a, b) in probs])
+    exp = np.array(list(probs.values())) * R
+    assert obs.sum() == R
+    assert (((obs - exp) ** 2) / exp).sum() < stats.chi2.ppf(1 - 1e-4, len(exp) - 1)
+
+
+def test_weighted_slot0_marginal_m25_and_window():
+    """Slot 0 is drawn with probability w_i / W over the m = 25 most recent candidates;
+    older entries are never candidates."""
+    rng = np.random.default_rng(3)
+    w = [int(x) for x in np.clip(np.rint(np.exp(rng.standard_normal(25)) * 4096), 1, 65536)]
+    g, t, ew, cnt = _weighted_graph(w, extra_older=40)
+    R = 100000
+    o = oracle.sample_hop(g, np.zeros(R, np.int32), np.full(R, t, np.int64), 10, oracle.WEIGHTED, 4, 0,
+                          m=25, edge_weight=ew, threads=4)
+    cand = cnt - 1 - o["nbr"]
+    assert cand.min() >= 0 and cand.max() < 25
+    assert all(len(set(row)) == 10 for row in cand[:2000].tolist())
+    obs = np.bincount(cand[:, 0], minlength=25)
+    exp = np.array(w) / sum(w) * R
+    assert (((obs - exp) ** 2) / exp).sum() < stats.chi2.ppf(1 - 1e-4, 24)
+
+
+def test_weighted_equal_weights_is_uniform_and_dominant_weight():
+    g, t, ew, cnt = _weighted_graph([7] * 5)
+    R = 100000
+    o = oracle.sample_hop(g, np.zeros(R, np.int32), np.full(R, t, np.int64), 2, oracle.WEIGHTED, 12, 0,
+                          m=5, edge_weight=ew, threads=4)
+    cand = cnt - 1 - o["nbr"]
+    code = cand[:, 0] * 5 + cand[:, 1]
+    pairs = [a * 5 + b for a in range(5) for b in range(5) if a != b]
+    obs = np.bincount(code, minlength=25)[pairs]
+    assert obs.sum() == R
+    assert (((obs - R / 20) ** 2) / (R / 20)).sum() < stats.chi2.ppf(1 - 1e-4, 19)
+    w = [1, 1, 60000, 1, 1, 1]
+    g, t, ew, cnt = _weighted_graph(w)
+    o = oracle.sample_hop(g, np.zeros(R, np.int32), np.full(R, t, np.int64), 2, oracle.WEIGHTED, 13, 0,
+                          m=6, edge_weight=ew, threads=4)
+    first = cnt - 1 - o["nbr"][:, 0]
+    p = 60000 / 60005
+    assert abs((first == 2).mean() - p) < 5 * np.sqrt(p * (1 - p) / R)
+
+
+def test_weighted_inclusion_probabilities_by_enumeration():
+    """m = 6, k = 3 (and c = k + 1): inclusion probabilities from enumerating every
+    ordered outcome of successive sampling."""
+    for w, k in (([3, 1, 4, 1, 5, 9], 3), ([2, 7, 1, 8], 3)):
+        g, t, ew, cnt = _weighted_graph(w)
+        R = 100000
+        o = oracle.sample_hop(g, np.zeros(R, np.int32), np.full(R, t, np.int64), k, oracle.WEIGHTED, 31, 1,
+                              m=len(w), edge_weight=ew, threads=4)
+        cand = cnt - 1 - o["nbr"]
+        probs = _successive_probs(w, k)
+        for i in range(len(w)):
+            p = sum(pr for seq, pr in probs.items() if i in seq)
+            f = np.any(cand == i, axis=1).mean()
+            assert abs(f - p) < 5 * np.sqrt(p * (1 - p) / R) + 1e-9
+
+
+def test_weighted_few_candidates_returns_all_in_candidate_order():
+    g, t, ew, cnt = _weighted_graph([9, 1, 5])
+    o = oracle.sample_hop(g, np.zeros(3, np.int32), np.full(3, t, np.int64), 4, oracle.WEIGHTED, 1, 0,
+                          m=25, edge_weight=ew)
+    assert np.all(o["count"] == 3)
+    assert np.all(o["nbr"][:, :3] == np.array([2, 1, 0])) and np.all(o["nbr"][:, 3] == -1)
+
+
+# --------------------------------------------------------------------------- two hops
+@pytest.mark.parametrize("policy", [oracle.RECENT, oracle.UNIFORM, oracle.WEIGHTED])
+def test_two_hop_composition(policy):
+    """Hop 2 of slot q is a 1-hop query on (nbr1[q], ts1[q]) (Alg. 1 layer loop), so every
+    second-hop sample is strictly earlier than the first-hop interaction it hangs off."""
+    rng = np.random.default_rng(21)
+    src, dst, ts, eid = _random_events(rng, 30, 4000, 5000, True)
+    src, dst = np.concatenate([src, dst]), np.concatenate([dst, src])
+    ts, eid = np.concatenate([ts, ts]), np.concatenate([eid, eid])
+    g = oracle.tcsr_build(src, dst, ts, eid, 30)
+    ew = rng.integers(1, 1 << 16, 4000).astype(np.uint32)
+    roots = rng.integers(0, 30, 64).astype(np.int32)
+    times = rng.integers(0, 5000, 64).astype(np.int64)
+    k = 4
+    h = oracle.sample_temporal(g, roots, times, k, 2, policy, seed=6, m=9, edge_weight=ew)
+    assert h[1]["nbr"].shape == (64 * k, k)
+    one = oracle.sample_hop(g, h[0]["nbr"].ravel(), h[0]["ts"].ravel(), k, policy, 6, 1, m=9, edge_weight=ew)
+    for name in ("nbr", "eid", "ts", "count"):
+        assert np.array_equal(h[1][name], one[name])
+    flat_valid = h[0]["nbr"].ravel() >= 0
+    assert np.all(h[1]["count"][~flat_valid] == 0)
+    parent_t = h[0]["ts"].ravel()[:, None]
+    valid2 = h[1]["nbr"] >= 0
+    assert np.all((h[1]["ts"] < parent_t)[valid2])
+    # every sampled (root, nbr, eid, ts) is an entry of the event list
+    events = set(zip(src.tolist(), dst.tolist(), eid.tolist(), ts.tolist()))
+    r1 = np.repeat(h[0]["nbr"].ravel(), k).reshape(-1, k)
+    for a, b, c, d in zip(r1[valid2], h[1]["nbr"][valid2], h[1]["eid"][valid2], h[1]["ts"][valid2]):
+        assert (int(a), int(b), int(c), int(d)) in events
+
+
+# --------------------------------------------------------------------------- gather + cache
+@pytest.mark.parametrize("dtype,dim,pad", [(np.float32, 16, 0), (np.float16, 172, 0), (np.float16, 186, 6),
+                                           (np.float32, 413, 3)])
+def test_gather_equals_numpy_take(dtype, dim, pad):
+    rng = np.random.default_rng(8)
+    rows = 500
+    full = rng.standard_normal((rows, dim + pad)).astype(dtype)
+    table = full[:, :dim]                                  # a padded row pitch
+    ids = rng.integers(0, rows, 2000).astype(np.int32)
+    ids[::7] = -1
+    out = oracle.gather(table, ids, threads=3)
+    want = np.take(table, np.maximum(ids, 0), axis=0)
+    want[ids < 0] = 0
+    assert out.tobytes() == want.tobytes()
+    with pytest.raises(ValueError):
+        oracle.gather(table, np.array([rows], np.int32))
+
+
+def test_cache_residents_and_hit_accounting():
+    rows, cap = 1000, 200
+    res = oracle.cache_random_residents(rows, cap, seed=5)
+    assert len(set(res.tolist())) == cap and res.min() >= 0 and res.max() < rows
+    # the draw is the same partial Fisher-Yates as the uniform policy
+    a = list(range(rows))
+    for j in range(cap):
+        r = j + ((oracle.draw64(5, 0x43414348, j, 0) * (rows - j)) >> 64)
+        a[j], a[r] = a[r], a[j]
+    assert res.tolist() == a[:cap]
+    rng = np.random.default_rng(1)
+    ids = rng.integers(-1, rows, 5000).astype(np.int32)
+    hits, misses = oracle.cache_hits(res, rows, ids)
+    assert hits == int(np.isin(ids, res).sum())
+    assert hits + misses == int((ids >= 0).sum())
+    # first-element marginal is uniform over the rows
+    firsts = np.array([oracle.cache_random_residents(50, 1, seed=s)[0] for s in range(20000)])
+    obs = np.bincount(firsts, minlength=50)
+    assert (((obs - 400) ** 2) / 400).sum() < stats.chi2.ppf(1 - 1e-4, 49)
