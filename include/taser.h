@@ -1,0 +1,207 @@
+/*
+ * taser.h — C ABI of the MI355X (gfx950) temporal neighbor finder and feature
+ * gather: the mini-batch generation hot path of TASER (arXiv 2402.05396,
+ * Sec. 2.1 "Neighbor Finder", Sec. 3.3 "GPU Temporal Neighbor Finding",
+ * Sec. 3.4 "GPU Feature Caching", Alg. 1-3).
+ *
+ * Conventions shared by every call
+ *   - Plain pointers and sizes only. Each pointer argument says "device" or
+ *     "host". Device pointers must be valid on the current HIP device.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Unless a call says otherwise it only enqueues work on that stream and
+ *     returns without waiting for it.
+ *   - Ownership: the caller owns every input and output buffer. The library
+ *     owns the opaque handles (and scratch memory inside them), released only
+ *     by the matching *_free call. A handle must not be used by two calls that
+ *     overlap in time on different streams.
+ *   - Return value: TASER_OK (0) or a negative taser_status. Arguments are
+ *     validated on the host before anything is launched; on error nothing has
+ *     been enqueued and taser_last_error() describes the problem.
+ *   - Padding: an unused output slot holds nbr = -1, eid = -1, ts = 0; a
+ *     negative id given to a gather produces a row of zero bytes.
+ */
+#ifndef TASER_H
+#define TASER_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct taser_tcsr taser_tcsr;   /* time-sorted CSR in device memory  */
+typedef struct taser_cache taser_cache; /* device cache over a host table    */
+
+enum taser_status {
+    TASER_OK = 0,
+    TASER_E_ARG = -1,         /* null pointer, non-positive size, bad enum          */
+    TASER_E_RANGE = -2,       /* a size or id outside the supported/declared range  */
+    TASER_E_OOM = -3,         /* device or host allocation failed                   */
+    TASER_E_HIP = -4,         /* a HIP runtime call failed                          */
+    TASER_E_UNSUPPORTED = -5  /* valid request this build does not implement        */
+};
+
+enum taser_policy {
+    TASER_RECENT = 0,   /* most recent neighbor finder   (Sec. 2.1, Alg. 2)              */
+    TASER_UNIFORM = 1,  /* uniform, without replacement  (Sec. 2.1, Alg. 2)              */
+    TASER_WEIGHTED = 2  /* n of the m most recent, by given weights (Alg. 1, 2nd draw)   */
+};
+
+enum taser_build_flags {
+    TASER_INPUT_ON_DEVICE = 1u /* src/dst/ts/eid are device pointers (default: host) */
+};
+
+#define TASER_MAX_K 64    /* neighbors kept per root and hop              */
+#define TASER_MAX_M 64    /* candidate window of the weighted policy      */
+#define TASER_MAX_HOPS 3
+
+/* ---------------------------------------------------------------------------
+ * T-CSR (Sec. 3.3: the dynamic graph is stored with every node's outgoing
+ * neighbors sorted by timestamp; Sec. 2.1: N(v,t) is defined over the edges
+ * leaving v).
+ *
+ * Groups the `num_entries` entries (src[i] -> dst[i] at ts[i], edge id eid[i])
+ * by src and orders each group by (ts, input position): a stable sort, so the
+ * result is unique. The library is direction-agnostic; a caller that queries
+ * both endpoints of an interaction passes it in both directions.
+ *
+ *   src, dst   int32[num_entries], node ids in [0, num_nodes)   host (or device
+ *   ts         int64[num_entries]                                with the flag)
+ *   eid        int32[num_entries], or NULL meaning eid[i] = i
+ *   num_entries in [0, 2^31 - 1), num_nodes in [1, 2^31 - 1)
+ *   out        receives a new handle
+ *
+ * Inputs are only read. This call synchronizes `hip_stream` before returning
+ * (it reads back the sort plan and the id-range check), so host inputs may be
+ * released immediately. Errors: TASER_E_RANGE if any src id is outside
+ * [0, num_nodes) (dst ids are carried, not interpreted, and are not checked).
+ * ------------------------------------------------------------------------- */
+int taser_tcsr_build(const int32_t* src, const int32_t* dst, const int64_t* ts,
+                     const int32_t* eid, int64_t num_entries, int32_t num_nodes,
+                     uint32_t flags, void* hip_stream, taser_tcsr** out);
+
+/* Size of a built graph (either out-pointer may be NULL). */
+int taser_tcsr_size(const taser_tcsr* g, int64_t* num_entries, int32_t* num_nodes);
+
+/* Canonical view for inspection and tests: writes the T-CSR as plain arrays
+ * into caller-allocated device buffers indptr int64[num_nodes+1], nbr
+ * int32[E'], ts int64[E'], eid int32[E'] (the sampler itself reads a packed
+ * layout of the library's own). Any of the four may be NULL to skip it. */
+int taser_tcsr_view(const taser_tcsr* g, int64_t* indptr, int32_t* nbr, int64_t* ts, int32_t* eid,
+                    void* hip_stream);
+
+void taser_tcsr_free(taser_tcsr* g);
+
+/* ---------------------------------------------------------------------------
+ * Temporal neighbor finding over one or more hops (Sec. 2.1; Alg. 2; the layer
+ * loop of Alg. 1).
+ *
+ * Hop 0 has num_roots roots (roots[i], times[i]). For a root (v, t) let cnt be
+ * the number of entries of v's list with ts < t (strictly). Output row i of a
+ * hop has k slots:
+ *   TASER_RECENT    slot j = entry cnt-1-j, for j < min(k, cnt).
+ *   TASER_UNIFORM   cnt <= k: as TASER_RECENT. Otherwise k distinct entries,
+ *                   a uniformly random ordered k-subset of the cnt valid ones,
+ *                   drawn by a partial Fisher-Yates shuffle with one Philox
+ *                   4x32-10 draw per slot keyed by (seed, hop, root index,
+ *                   slot): r = j + floor(draw * (cnt - j) / 2^64).
+ *   TASER_WEIGHTED  candidates = the c = min(m, cnt) most recent entries,
+ *                   candidate i = entry cnt-1-i with weight
+ *                   edge_weight[eid] (must be >= 1). c <= k: all candidates in
+ *                   that order. Otherwise k successive draws without
+ *                   replacement, each proportional to the remaining weights:
+ *                   x = floor(draw * W / 2^64), first remaining candidate
+ *                   whose running weight sum exceeds x.
+ * count[i] = number of filled (leading) slots; the rest are padding.
+ * Hop h+1 has one root per slot of hop h, root index i*k + j, node = the
+ * sampled neighbor and query time = the sampled interaction's timestamp; a
+ * padding slot is a root with no neighbors. A root with a negative node id is
+ * treated the same way. Results depend only on (graph, root, time, root
+ * index, seed): they are reproducible and independent of launch shape.
+ *
+ *   roots int32[num_roots], times int64[num_roots]              device
+ *   k in [1, TASER_MAX_K], hops in [1, TASER_MAX_HOPS], num_roots * k^hops < 2^31
+ *   m in [1, TASER_MAX_M] and edge_weight uint32[max eid + 1] (device):
+ *     TASER_WEIGHTED only, ignored otherwise (edge_weight may then be NULL)
+ *   out   host array of `hops` structs of caller-allocated device buffers;
+ *         hop h holds R_h = num_roots * k^h roots:
+ *         nbr int32[R_h*k], eid int32[R_h*k], ts int64[R_h*k], count int32[R_h]
+ * A root whose node id is >= num_nodes is treated like a negative one.
+ * Edge ids of the graph must index edge_weight (not checked).
+ * ------------------------------------------------------------------------- */
+typedef struct taser_hop_out {
+    int32_t* nbr;
+    int32_t* eid;
+    int64_t* ts;
+    int32_t* count;
+} taser_hop_out;
+
+int taser_sample_temporal(const taser_tcsr* g, const int32_t* roots, const int64_t* times,
+                          int64_t num_roots, int32_t k, int32_t hops, int32_t policy,
+                          uint64_t seed, int32_t m, const uint32_t* edge_weight,
+                          const taser_hop_out* out, void* hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * Feature slicing from a table in device memory (Sec. 3.4; Alg. 3 "serve
+ * x_e"): out row i = the row_bytes bytes of table row ids[i]; ids[i] < 0 gives
+ * a zero row. The output is dense (row i at byte offset i * row_bytes).
+ *
+ *   table        device, `rows` rows, row r at byte offset r * pitch_bytes
+ *   row_bytes    > 0, even; pitch_bytes >= row_bytes, even
+ *   ids          int32[n], device; an id >= rows is served like a negative one
+ *   out          device, n * row_bytes bytes, must not overlap the table
+ * Rows whose size, pitch and base addresses share a 16-, 8- or 4-byte
+ * alignment are moved with loads and stores of that width.
+ * ------------------------------------------------------------------------- */
+int taser_gather_features(const void* table, int64_t rows, int32_t row_bytes,
+                          int64_t pitch_bytes, const int32_t* ids, int64_t n, void* out,
+                          void* hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * Device cache of hot feature rows over a table in pinned host memory
+ * (Sec. 3.4, Alg. 3: k rows live in device memory, the rest are read from host
+ * memory over the bus; the cache line is one row).
+ *
+ * taser_cache_init copies `capacity_rows` rows into device memory and builds a
+ * hashed id -> slot index there.
+ *   host_table      host, allocated page-locked and device-mapped
+ *                   (hipHostMalloc / a pinned torch tensor); it must outlive
+ *                   the handle. TASER_E_ARG if it is not such memory.
+ *   rows, row_bytes, pitch_bytes   as for taser_gather_features; row_bytes % 4 == 0
+ *   capacity_rows   in [0, rows]
+ *   resident_ids    host int32[capacity_rows], distinct, in [0, rows); or NULL:
+ *                   the first capacity_rows elements of a partial Fisher-Yates
+ *                   shuffle of 0..rows-1 with draw j keyed (seed, hop tag
+ *                   0x43414348, root index j, slot 0) ("randomly cache k
+ *                   features", Alg. 3)
+ *   staging_rows    rows of per-call device staging (>= 0): rows that miss are
+ *                   fetched from host memory once per call into it, however
+ *                   often the call requests them; requests that find it full
+ *                   read host memory directly.
+ * This call synchronizes `hip_stream` before returning.
+ *
+ * taser_cache_lookup serves n rows into the dense `out` exactly like
+ * taser_gather_features over the host table; which rows are resident never
+ * changes the bytes served. hit_miss (device uint64[2], may be NULL) is
+ * incremented by the number of requests with a resident id ([0]) and with a
+ * valid non-resident id ([1]).
+ * ------------------------------------------------------------------------- */
+int taser_cache_init(const void* host_table, int64_t rows, int32_t row_bytes,
+                     int64_t pitch_bytes, int64_t capacity_rows, const int32_t* resident_ids,
+                     uint64_t seed, int64_t staging_rows, void* hip_stream, taser_cache** out);
+
+int taser_cache_lookup(taser_cache* c, const int32_t* ids, int64_t n, void* out,
+                       uint64_t* hit_miss, void* hip_stream);
+
+/* Copies the resident row ids (slot order) to host int32[capacity_rows]. */
+int taser_cache_residents(const taser_cache* c, int32_t* resident_ids_host);
+
+void taser_cache_free(taser_cache* c);
+
+/* Message for the most recent error on the calling thread (static storage). */
+const char* taser_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TASER_H */

@@ -1,0 +1,255 @@
+"""MI355X-native temporal neighbor finder + feature gather (TASER, arXiv 2402.05396).
+
+Thin ctypes binding over ``libtaser.so`` (C ABI declared in ``include/taser.h``).
+The functions here carry the same names as the C entry points and only marshal
+arguments: torch supplies device memory and the current stream, every step of
+the path runs in the library's HIP kernels. There is no fallback: if the
+library has not been built, or no GPU is present, calls raise.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtaser.so")
+
+RECENT, UNIFORM, WEIGHTED = 0, 1, 2
+INPUT_ON_DEVICE = 1
+MAX_K, MAX_M, MAX_HOPS = 64, 64, 3
+
+EXPORTS = ("taser_tcsr_build", "taser_tcsr_size", "taser_tcsr_view", "taser_tcsr_free", "taser_sample_temporal",
+           "taser_gather_features", "taser_cache_init", "taser_cache_lookup", "taser_cache_residents",
+           "taser_cache_free", "taser_last_error")
+
+
+class TaserError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"taser error {code}: {message}")
+        self.code = code
+
+
+class _HopOut(ctypes.Structure):
+    _fields_ = [("nbr", ctypes.c_void_p), ("eid", ctypes.c_void_p), ("ts", ctypes.c_void_p),
+                ("count", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2402_05396_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, u32, u64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32, ctypes.c_uint64
+        L.taser_tcsr_build.argtypes = [vp, vp, vp, vp, i64, i32, u32, vp, ctypes.POINTER(vp)]
+        L.taser_tcsr_size.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i32)]
+        L.taser_tcsr_view.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.taser_tcsr_free.argtypes = [vp]
+        L.taser_tcsr_free.restype = None
+        L.taser_sample_temporal.argtypes = [vp, vp, vp, i64, i32, i32, i32, u64, i32, vp,
+                                            ctypes.POINTER(_HopOut), vp]
+        L.taser_gather_features.argtypes = [vp, i64, i32, i64, vp, i64, vp, vp]
+        L.taser_cache_init.argtypes = [vp, i64, i32, i64, i64, vp, u64, i64, vp, ctypes.POINTER(vp)]
+        L.taser_cache_lookup.argtypes = [vp, vp, i64, vp, vp, vp]
+        L.taser_cache_residents.argtypes = [vp, vp]
+        L.taser_cache_free.argtypes = [vp]
+        L.taser_cache_free.restype = None
+        L.taser_last_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def last_error():
+    return lib().taser_last_error().decode()
+
+
+def _check(rc):
+    if rc != 0:
+        raise TaserError(rc, last_error())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _want(t, dtype, name, cuda=True):
+    if t.dtype != dtype or not t.is_contiguous() or t.is_cuda != cuda:
+        raise TypeError(f"{name}: expected a contiguous {'device' if cuda else 'host'} tensor of {dtype}")
+    return t
+
+
+class TCSR:
+    """Owner of a taser_tcsr handle."""
+
+    def __init__(self, handle, num_entries, num_nodes):
+        self.handle, self.num_entries, self.num_nodes = handle, num_entries, num_nodes
+
+    def free(self):
+        if self.handle:
+            lib().taser_tcsr_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def tcsr_build(src, dst, ts, eid, num_nodes, stream=None):
+    """taser_tcsr_build. src/dst/eid int32, ts int64; all on the GPU or all on the host."""
+    on_dev = src.is_cuda
+    _want(src, torch.int32, "src", on_dev)
+    _want(dst, torch.int32, "dst", on_dev)
+    _want(ts, torch.int64, "ts", on_dev)
+    if eid is not None:
+        _want(eid, torch.int32, "eid", on_dev)
+    n = src.numel()
+    if dst.numel() != n or ts.numel() != n or (eid is not None and eid.numel() != n):
+        raise ValueError("src, dst, ts, eid must have the same length")
+    h = ctypes.c_void_p()
+    _check(lib().taser_tcsr_build(_ptr(src), _ptr(dst), _ptr(ts), _ptr(eid), n, num_nodes,
+                                  INPUT_ON_DEVICE if on_dev else 0, _stream(stream), ctypes.byref(h)))
+    return TCSR(h, n, num_nodes)
+
+
+def tcsr_size(g):
+    """taser_tcsr_size -> (num_entries, num_nodes)."""
+    ne, nn = ctypes.c_int64(), ctypes.c_int32()
+    _check(lib().taser_tcsr_size(g.handle, ctypes.byref(ne), ctypes.byref(nn)))
+    return ne.value, nn.value
+
+
+def tcsr_view(g, stream=None):
+    """taser_tcsr_view -> (indptr, nbr, ts, eid) as plain device tensors."""
+    n, dev = g.num_entries, "cuda"
+    indptr = torch.empty(g.num_nodes + 1, dtype=torch.int64, device=dev)
+    nbr = torch.empty(n, dtype=torch.int32, device=dev)
+    ts = torch.empty(n, dtype=torch.int64, device=dev)
+    eid = torch.empty(n, dtype=torch.int32, device=dev)
+    _check(lib().taser_tcsr_view(g.handle, _ptr(indptr), _ptr(nbr), _ptr(ts), _ptr(eid), _stream(stream)))
+    return indptr, nbr, ts, eid
+
+
+def tcsr_free(g):
+    g.free()
+
+
+def sample_temporal(g, roots, times, k, hops, policy, seed, m=0, edge_weight=None, out=None, stream=None):
+    """taser_sample_temporal. Returns a list of `hops` dicts of device tensors
+    nbr/eid/ts [R_h, k] and count [R_h] (allocated here unless `out` is given)."""
+    _want(roots, torch.int32, "roots")
+    _want(times, torch.int64, "times")
+    if edge_weight is not None:
+        _want(edge_weight, torch.int32, "edge_weight (uint32 bits in an int32 tensor)")
+    n = roots.numel()
+    if times.numel() != n:
+        raise ValueError("roots and times must have the same length")
+    if out is None:
+        out, r = [], n
+        for _ in range(max(hops, 0)):
+            out.append(dict(nbr=torch.empty((r, k), dtype=torch.int32, device=roots.device),
+                            eid=torch.empty((r, k), dtype=torch.int32, device=roots.device),
+                            ts=torch.empty((r, k), dtype=torch.int64, device=roots.device),
+                            count=torch.empty((r,), dtype=torch.int32, device=roots.device)))
+            r *= k
+    arr = (_HopOut * max(len(out), 1))()
+    r = n
+    for h, o in enumerate(out):
+        for name, dt, cnt in (("nbr", torch.int32, r * k), ("eid", torch.int32, r * k), ("ts", torch.int64, r * k),
+                              ("count", torch.int32, r)):
+            _want(o[name], dt, f"out[{h}].{name}")
+            if o[name].numel() < cnt:
+                raise ValueError(f"out[{h}].{name} is too small")
+            setattr(arr[h], name, o[name].data_ptr())
+        r *= k
+    _check(lib().taser_sample_temporal(g.handle, _ptr(roots), _ptr(times), n, k, hops, policy, seed, m,
+                                       _ptr(edge_weight), arr, _stream(stream)))
+    return out
+
+
+def gather_features(table, ids, out=None, row_elems=None, stream=None):
+    """taser_gather_features. table: 2-D device tensor whose rows are contiguous
+    (row pitch = table.stride(0)); the first `row_elems` columns are gathered."""
+    if table.dim() != 2 or table.stride(1) != 1 or not table.is_cuda:
+        raise TypeError("table: expected a 2-D device tensor with contiguous rows")
+    _want(ids, torch.int32, "ids")
+    es = table.element_size()
+    d = table.shape[1] if row_elems is None else row_elems
+    n = ids.numel()
+    if out is None:
+        out = torch.empty((n, d), dtype=table.dtype, device=table.device)
+    elif out.dtype != table.dtype or not out.is_contiguous() or out.numel() < n * d:
+        raise TypeError("out: expected a contiguous device tensor of the table's dtype with n*d elements")
+    _check(lib().taser_gather_features(_ptr(table), table.shape[0], d * es, table.stride(0) * es, _ptr(ids), n,
+                                       _ptr(out), _stream(stream)))
+    return out
+
+
+class Cache:
+    """Owner of a taser_cache handle (keeps the pinned host table alive)."""
+
+    def __init__(self, handle, host_table, capacity, row_elems):
+        self.handle, self.host_table, self.capacity, self.row_elems = handle, host_table, capacity, row_elems
+
+    def free(self):
+        if self.handle:
+            lib().taser_cache_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def cache_init(host_table, capacity_rows, resident_ids=None, seed=0, staging_rows=0, stream=None):
+    """taser_cache_init. host_table: 2-D pinned host tensor with contiguous rows;
+    resident_ids: host int32 tensor or None."""
+    if host_table.dim() != 2 or host_table.stride(1) != 1 or host_table.is_cuda:
+        raise TypeError("host_table: expected a 2-D host tensor with contiguous rows")
+    if resident_ids is not None:
+        _want(resident_ids, torch.int32, "resident_ids", cuda=False)
+        if resident_ids.numel() != capacity_rows:
+            raise ValueError("resident_ids must hold capacity_rows ids")
+    es = host_table.element_size()
+    h = ctypes.c_void_p()
+    _check(lib().taser_cache_init(_ptr(host_table), host_table.shape[0], host_table.shape[1] * es,
+                                  host_table.stride(0) * es, capacity_rows, _ptr(resident_ids), seed,
+                                  staging_rows, _stream(stream), ctypes.byref(h)))
+    return Cache(h, host_table, capacity_rows, host_table.shape[1])
+
+
+def cache_lookup(c, ids, out=None, hit_miss=None, stream=None):
+    """taser_cache_lookup. hit_miss: device int64[2] tensor that is incremented, or None."""
+    _want(ids, torch.int32, "ids")
+    n = ids.numel()
+    if out is None:
+        out = torch.empty((n, c.row_elems), dtype=c.host_table.dtype, device=ids.device)
+    elif out.dtype != c.host_table.dtype or not out.is_contiguous() or out.numel() < n * c.row_elems:
+        raise TypeError("out: expected a contiguous device tensor of the table's dtype with n*d elements")
+    if hit_miss is not None:
+        _want(hit_miss, torch.int64, "hit_miss")
+    _check(lib().taser_cache_lookup(c.handle, _ptr(ids), n, _ptr(out), _ptr(hit_miss), _stream(stream)))
+    return out
+
+
+def cache_residents(c):
+    out = torch.empty(c.capacity, dtype=torch.int32)
+    _check(lib().taser_cache_residents(c.handle, _ptr(out)))
+    return out
+
+
+def cache_free(c):
+    c.free()

@@ -1,0 +1,339 @@
+// Device cache of hot feature rows over a table in pinned host memory
+// (TASER, arXiv 2402.05396, Sec. 3.4 and Alg. 3: a fixed budget of rows lives
+// in device memory with a cache line of one row; other rows are read from host
+// memory over the bus without an intermediate copy).
+//
+// Layout in device memory: `capacity` rows packed at a 4-byte-rounded pitch; an
+// open-addressing hash table id -> slot (linear probing, power-of-two size
+// >= 2 * capacity); and a per-call staging area so that a row which misses is
+// pulled over PCIe once per call however many requests name it (with skewed
+// access a hot non-resident row is otherwise re-read hundreds of times per
+// batch over a bus 100x slower than HBM).
+//
+// A lookup is four launches on the caller's stream:
+//   1. clear the per-call miss table;
+//   2. classify: every request probes the resident hash; a miss claims a slot
+//      of the miss table (compare-and-swap on the id, the slot index doubles as
+//      the staging row) — the outcome per request is written to `loc`;
+//   3. stage: one wave per claimed slot copies that row host -> staging;
+//   4. gather: the dense output is written from cache rows / staged rows /
+//      zero rows, or straight from host memory for requests that found the
+//      miss table full.
+// Which rows are resident only changes where bytes come from, never the bytes.
+#include <new>
+#include <vector>
+
+#include "gather_kernel.h"
+#include "taser_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int32_t kEmpty = -1;
+constexpr int32_t kLocZero = -1;                   // request with a negative id
+constexpr int32_t kLocHost = INT32_MIN;            // read the host row directly
+constexpr int kMaxMissProbes = 128;
+constexpr uint32_t kTagCache = 0x43414348u;        // hop tag of the residency shuffle
+
+__host__ __device__ inline uint32_t hash_id(int32_t id, uint32_t mask) {
+    uint32_t h = (uint32_t)id * 0x9E3779B1u;
+    h ^= h >> 15;
+    return h & mask;
+}
+// loc encoding: >= 0 cache slot; kLocZero; kLocHost; otherwise -2 - staging slot
+__host__ __device__ inline int32_t loc_of_stage(uint32_t s) { return -2 - (int32_t)s; }
+
+}  // namespace
+
+struct taser_cache {
+    int64_t rows;
+    int32_t row_bytes;
+    int64_t pitch_bytes;        // of the host table
+    int64_t capacity;
+    const uint8_t* host_rows;   // device-visible address of the pinned host table
+    int32_t dev_pitch;          // pitch of cache_rows / stage_rows
+    uint8_t* cache_rows;        // device [capacity][dev_pitch]
+    int32_t* hash_key;          // device [hash_size], kEmpty or a resident id
+    int32_t* hash_slot;         // device [hash_size]
+    uint32_t hash_mask;
+    uint8_t* stage_rows;        // device [miss_size][dev_pitch]
+    int32_t* miss_key;          // device [miss_size], cleared per lookup
+    uint32_t miss_size;         // 0 or a power of two
+    int32_t* loc;               // device [loc_capacity], per-request outcome
+    int64_t loc_capacity;
+    std::vector<int32_t>* residents;   // host copy, slot order
+};
+
+namespace {
+
+__global__ __launch_bounds__(kThreads) void fill_kernel(int32_t* a, uint32_t n, int32_t v) {
+    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
+    if (i < n) a[i] = v;
+}
+
+__global__ __launch_bounds__(kThreads) void classify_kernel(
+    const int32_t* __restrict__ ids, int64_t n, int64_t rows, const int32_t* __restrict__ hash_key,
+    const int32_t* __restrict__ hash_slot, uint32_t hash_mask, int32_t* miss_key, uint32_t miss_size,
+    int32_t* __restrict__ loc, unsigned long long* hit_miss) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    bool hit = false, miss = false;
+    if (i < n) {
+        const int32_t id = ids[i];
+        int32_t where = kLocZero;
+        if (id >= 0 && id < rows) {
+            uint32_t h = hash_id(id, hash_mask);
+            int32_t slot = -1;
+            for (;;) {                               // the table is never full: the loop ends at an empty key
+                const int32_t key = hash_key[h];
+                if (key == id) { slot = hash_slot[h]; break; }
+                if (key == kEmpty) break;
+                h = (h + 1) & hash_mask;
+            }
+            if (slot >= 0) {
+                hit = true;
+                where = slot;
+            } else {
+                miss = true;
+                where = kLocHost;
+                if (miss_size) {
+                    uint32_t s = hash_id(id, miss_size - 1);
+                    for (int probe = 0; probe < kMaxMissProbes; ++probe) {
+                        int32_t key = miss_key[s];
+                        if (key == kEmpty) key = atomicCAS(&miss_key[s], kEmpty, id);
+                        if (key == kEmpty || key == id) { where = loc_of_stage(s); break; }
+                        s = (s + 1) & (miss_size - 1);
+                    }
+                }
+            }
+        }
+        loc[i] = where;
+    }
+    if (hit_miss) {
+        const unsigned long long hits = __ballot(hit), misses = __ballot(miss);
+        if ((threadIdx.x & (kWave - 1)) == 0) {
+            if (hits) atomicAdd(&hit_miss[0], (unsigned long long)__popcll(hits));
+            if (misses) atomicAdd(&hit_miss[1], (unsigned long long)__popcll(misses));
+        }
+    }
+}
+
+// One wave per miss-table slot: copy the claimed row from host memory.
+__global__ __launch_bounds__(kThreads) void stage_kernel(const int32_t* __restrict__ miss_key, uint32_t miss_size,
+                                                         const uint8_t* __restrict__ host_rows, int64_t pitch_bytes,
+                                                         int32_t row_words, uint8_t* __restrict__ stage_rows,
+                                                         int32_t dev_pitch) {
+    const uint32_t s = blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
+    if (s >= miss_size) return;
+    const int32_t id = miss_key[s];
+    if (id < 0) return;
+    const uint32_t* from = reinterpret_cast<const uint32_t*>(host_rows + (int64_t)id * pitch_bytes);
+    uint32_t* to = reinterpret_cast<uint32_t*>(stage_rows + (int64_t)s * dev_pitch);
+    for (int32_t w = threadIdx.x & (kWave - 1); w < row_words; w += kWave) to[w] = from[w];
+}
+
+struct CacheSource {
+    const int32_t* loc;
+    const int32_t* ids;
+    const uint8_t* cache_rows;
+    const uint8_t* stage_rows;
+    int32_t dev_pitch;
+    const uint8_t* host_rows;
+    int64_t pitch_bytes;
+    __device__ __forceinline__ const uint8_t* row(int64_t i) const {
+        const int32_t where = loc[i];
+        if (where >= 0) return cache_rows + (int64_t)where * dev_pitch;
+        if (where == kLocZero) return nullptr;
+        if (where == kLocHost) return host_rows + (int64_t)ids[i] * pitch_bytes;
+        return stage_rows + (int64_t)(-2 - where) * dev_pitch;
+    }
+};
+
+// Philox4x32-10 on the host, for the default residency draw only.
+uint64_t host_draw64(uint64_t seed, uint32_t hop, uint64_t root, uint32_t slot) {
+    uint32_t c[4] = {(uint32_t)root, (uint32_t)(root >> 32), slot, hop};
+    uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c[0], p1 = (uint64_t)0xCD9E8D57u * c[2];
+        const uint32_t a = (uint32_t)(p1 >> 32) ^ c[1] ^ k0, b = (uint32_t)(p0 >> 32) ^ c[3] ^ k1;
+        c[0] = a; c[1] = (uint32_t)p1; c[2] = b; c[3] = (uint32_t)p0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return ((uint64_t)c[1] << 32) | c[0];
+}
+
+uint32_t pow2_at_least(uint64_t x) {
+    uint32_t p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+void destroy(taser_cache* c) {
+    if (!c) return;
+    (void)hipFree(c->cache_rows);
+    (void)hipFree(c->hash_key);
+    (void)hipFree(c->hash_slot);
+    (void)hipFree(c->stage_rows);
+    (void)hipFree(c->miss_key);
+    (void)hipFree(c->loc);
+    delete c->residents;
+    delete c;
+}
+
+}  // namespace
+
+extern "C" int taser_cache_init(const void* host_table, int64_t rows, int32_t row_bytes, int64_t pitch_bytes,
+                                int64_t capacity_rows, const int32_t* resident_ids, uint64_t seed,
+                                int64_t staging_rows, void* hip_stream, taser_cache** out) {
+    if (!out) return taser_fail(TASER_E_ARG, "cache_init: null out");
+    *out = nullptr;
+    if (!host_table) return taser_fail(TASER_E_ARG, "cache_init: null host table");
+    if (rows < 1 || rows >= 0x7fffffffLL) return taser_fail(TASER_E_RANGE, "cache_init: rows = %lld outside [1, 2^31 - 1)", (long long)rows);
+    if (row_bytes <= 0 || (row_bytes & 3)) return taser_fail(TASER_E_ARG, "cache_init: row_bytes = %d must be a positive multiple of 4", row_bytes);
+    if (pitch_bytes < row_bytes || (pitch_bytes & 3)) return taser_fail(TASER_E_ARG, "cache_init: pitch_bytes = %lld must be a multiple of 4 and >= row_bytes", (long long)pitch_bytes);
+    if (capacity_rows < 0 || capacity_rows > rows) return taser_fail(TASER_E_RANGE, "cache_init: capacity_rows = %lld outside [0, rows]", (long long)capacity_rows);
+    if (staging_rows < 0 || staging_rows > ((int64_t)1 << 29)) return taser_fail(TASER_E_RANGE, "cache_init: staging_rows = %lld outside [0, 2^29]", (long long)staging_rows);
+    if ((uintptr_t)host_table & 3) return taser_fail(TASER_E_ARG, "cache_init: host table must be 4-byte aligned");
+
+    hipPointerAttribute_t attr;
+    hipError_t pe = hipPointerGetAttributes(&attr, host_table);
+    if (pe != hipSuccess || attr.type != hipMemoryTypeHost || !attr.devicePointer) {
+        (void)hipGetLastError();   // the query leaves a sticky error for ordinary host memory
+        return taser_fail(TASER_E_ARG, "cache_init: host table is not page-locked, device-mapped host memory");
+    }
+    hipStream_t stream = (hipStream_t)hip_stream;
+
+    taser_cache* c = new (std::nothrow) taser_cache();
+    if (!c) return taser_fail(TASER_E_OOM, "cache_init: host allocation failed");
+    *c = taser_cache{};
+    c->rows = rows;
+    c->row_bytes = row_bytes;
+    c->pitch_bytes = pitch_bytes;
+    c->capacity = capacity_rows;
+    c->host_rows = static_cast<const uint8_t*>(attr.devicePointer);
+    c->dev_pitch = row_bytes;
+    c->residents = new (std::nothrow) std::vector<int32_t>();
+    if (!c->residents) { destroy(c); return taser_fail(TASER_E_OOM, "cache_init: host allocation failed"); }
+
+    // ---- resident ids
+    std::vector<int32_t>& res = *c->residents;
+    try {
+        res.resize((size_t)capacity_rows);
+        if (resident_ids) {
+            std::vector<uint8_t> seen((size_t)rows, 0);
+            for (int64_t i = 0; i < capacity_rows; ++i) {
+                const int32_t id = resident_ids[i];
+                if (id < 0 || id >= rows || seen[(size_t)id]) {
+                    destroy(c);
+                    return taser_fail(TASER_E_RANGE, "cache_init: resident_ids[%lld] = %d is out of range or repeated", (long long)i, id);
+                }
+                seen[(size_t)id] = 1;
+                res[(size_t)i] = id;
+            }
+        } else {
+            // partial Fisher-Yates over 0..rows-1; `moved` holds the displaced values
+            std::vector<int32_t> a((size_t)rows);
+            for (int64_t i = 0; i < rows; ++i) a[(size_t)i] = (int32_t)i;
+            for (int64_t j = 0; j < capacity_rows; ++j) {
+                const uint64_t u = host_draw64(seed, kTagCache, (uint64_t)j, 0u);
+                const int64_t r = j + (int64_t)(((unsigned __int128)u * (uint64_t)(rows - j)) >> 64);
+                const int32_t t = a[(size_t)r];
+                a[(size_t)r] = a[(size_t)j];
+                a[(size_t)j] = t;
+                res[(size_t)j] = t;
+            }
+        }
+    } catch (const std::bad_alloc&) {
+        destroy(c);
+        return taser_fail(TASER_E_OOM, "cache_init: host allocation failed");
+    }
+
+    // ---- hash table id -> slot, built on the host and uploaded
+    const uint32_t hash_size = pow2_at_least((uint64_t)(capacity_rows > 8 ? capacity_rows : 8) * 2);
+    c->hash_mask = hash_size - 1;
+    std::vector<int32_t> h_key(hash_size, kEmpty), h_slot(hash_size, -1);
+    for (int64_t s = 0; s < capacity_rows; ++s) {
+        uint32_t h = hash_id(res[(size_t)s], c->hash_mask);
+        while (h_key[h] != kEmpty) h = (h + 1) & c->hash_mask;
+        h_key[h] = res[(size_t)s];
+        h_slot[h] = (int32_t)s;
+    }
+    c->miss_size = staging_rows > 0 ? pow2_at_least((uint64_t)staging_rows * 2) : 0;
+
+#define CACHE_TRY(expr)                                               \
+    do {                                                              \
+        hipError_t e_ = (expr);                                       \
+        if (e_ != hipSuccess) { destroy(c); return taser_fail_hip(e_, #expr); } \
+    } while (0)
+    int32_t* d_res = nullptr;
+    CACHE_TRY(hipMalloc((void**)&c->cache_rows, (size_t)(capacity_rows > 0 ? capacity_rows : 1) * c->dev_pitch));
+    CACHE_TRY(hipMalloc((void**)&c->hash_key, (size_t)hash_size * sizeof(int32_t)));
+    CACHE_TRY(hipMalloc((void**)&c->hash_slot, (size_t)hash_size * sizeof(int32_t)));
+    CACHE_TRY(hipMemcpyAsync(c->hash_key, h_key.data(), (size_t)hash_size * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+    CACHE_TRY(hipMemcpyAsync(c->hash_slot, h_slot.data(), (size_t)hash_size * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+    if (c->miss_size) {
+        CACHE_TRY(hipMalloc((void**)&c->stage_rows, (size_t)c->miss_size * c->dev_pitch));
+        CACHE_TRY(hipMalloc((void**)&c->miss_key, (size_t)c->miss_size * sizeof(int32_t)));
+    }
+    if (capacity_rows > 0) {
+        // fill the cache: a gather of the resident rows straight out of host memory
+        CACHE_TRY(hipMalloc((void**)&d_res, (size_t)capacity_rows * sizeof(int32_t)));
+        hipError_t e = hipMemcpyAsync(d_res, res.data(), (size_t)capacity_rows * sizeof(int32_t), hipMemcpyHostToDevice, stream);
+        int rc = TASER_OK;
+        if (e != hipSuccess) rc = taser_fail_hip(e, "hipMemcpyAsync(resident ids)");
+        if (rc == TASER_OK) rc = taser_launch_gather(c->host_rows, rows, row_bytes, pitch_bytes, d_res, capacity_rows, c->cache_rows, stream);
+        e = hipStreamSynchronize(stream);
+        (void)hipFree(d_res);
+        if (rc == TASER_OK && e != hipSuccess) rc = taser_fail_hip(e, "hipStreamSynchronize");
+        if (rc != TASER_OK) { destroy(c); return rc; }
+    }
+    CACHE_TRY(hipStreamSynchronize(stream));
+#undef CACHE_TRY
+    *out = c;
+    return TASER_OK;
+}
+
+extern "C" int taser_cache_lookup(taser_cache* c, const int32_t* ids, int64_t n, void* out, uint64_t* hit_miss,
+                                  void* hip_stream) {
+    if (!c) return taser_fail(TASER_E_ARG, "cache_lookup: null cache");
+    if (n < 0) return taser_fail(TASER_E_ARG, "cache_lookup: n = %lld", (long long)n);
+    if (n == 0) return TASER_OK;
+    if (!ids || !out) return taser_fail(TASER_E_ARG, "cache_lookup: null ids or out");
+    if ((uintptr_t)out & 3) return taser_fail(TASER_E_ARG, "cache_lookup: out must be 4-byte aligned");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (n > c->loc_capacity) {
+        // grows only; the old buffer may still be in use by earlier work on this stream
+        TASER_HIP_TRY(hipStreamSynchronize(stream));
+        (void)hipFree(c->loc);
+        c->loc = nullptr;
+        c->loc_capacity = 0;
+        TASER_HIP_TRY(hipMalloc((void**)&c->loc, (size_t)n * sizeof(int32_t)));
+        c->loc_capacity = n;
+    }
+    const int64_t blocks = (n + kThreads - 1) / kThreads;
+    if (blocks > 0x7fffffffLL) return taser_fail(TASER_E_RANGE, "cache_lookup: n too large");
+    if (c->miss_size)
+        hipLaunchKernelGGL(fill_kernel, dim3((c->miss_size + kThreads - 1) / kThreads), dim3(kThreads), 0, stream,
+                           c->miss_key, c->miss_size, kEmpty);
+    hipLaunchKernelGGL(classify_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, ids, n, c->rows, c->hash_key,
+                       c->hash_slot, c->hash_mask, c->miss_key, c->miss_size, c->loc,
+                       reinterpret_cast<unsigned long long*>(hit_miss));
+    if (c->miss_size)
+        hipLaunchKernelGGL(stage_kernel, dim3((c->miss_size + 3) / 4), dim3(kThreads), 0, stream, c->miss_key,
+                           c->miss_size, c->host_rows, c->pitch_bytes, c->row_bytes / 4, c->stage_rows, c->dev_pitch);
+    const CacheSource source{c->loc, ids, c->cache_rows, c->stage_rows, c->dev_pitch, c->host_rows, c->pitch_bytes};
+    const int align = taser_gather::common_alignment((uint64_t)c->row_bytes | (uint64_t)c->pitch_bytes |
+                                                     (uint64_t)(uintptr_t)c->host_rows | (uint64_t)(uintptr_t)out);
+    if (!taser_gather::launch(source, align, c->row_bytes, n, out, stream))
+        return taser_fail(TASER_E_RANGE, "cache_lookup: %lld rows of %d bytes exceed one launch", (long long)n, c->row_bytes);
+    TASER_HIP_TRY(hipGetLastError());
+    return TASER_OK;
+}
+
+extern "C" int taser_cache_residents(const taser_cache* c, int32_t* resident_ids_host) {
+    if (!c || (!resident_ids_host && c->capacity > 0)) return taser_fail(TASER_E_ARG, "cache_residents: null argument");
+    for (int64_t i = 0; i < c->capacity; ++i) resident_ids_host[i] = (*c->residents)[(size_t)i];
+    return TASER_OK;
+}
+
+extern "C" void taser_cache_free(taser_cache* c) { destroy(c); }

@@ -1,0 +1,44 @@
+// taser_gather_features: feature slicing from a table in device memory
+// (TASER, arXiv 2402.05396, Sec. 3.4 / Alg. 3: serve the feature row of every
+// requested id). A pure byte mover, bounded by HBM bandwidth.
+#include "gather_kernel.h"
+#include "taser_internal.h"
+
+namespace {
+
+struct TableSource {
+    const uint8_t* table;
+    int64_t pitch_bytes;
+    const int32_t* ids;
+    int64_t rows;
+    __device__ __forceinline__ const uint8_t* row(int64_t i) const {
+        const int32_t id = ids[i];
+        return (id < 0 || id >= rows) ? nullptr : table + (int64_t)id * pitch_bytes;
+    }
+};
+
+}  // namespace
+
+int taser_launch_gather(const void* table, int64_t rows, int32_t row_bytes, int64_t pitch_bytes, const int32_t* ids,
+                        int64_t n, void* out, hipStream_t stream) {
+    const int align = taser_gather::common_alignment((uint64_t)row_bytes | (uint64_t)pitch_bytes |
+                                                     (uint64_t)(uintptr_t)table | (uint64_t)(uintptr_t)out);
+    const TableSource source{static_cast<const uint8_t*>(table), pitch_bytes, ids, rows};
+    if (!taser_gather::launch(source, align, row_bytes, n, out, stream))
+        return taser_fail(TASER_E_RANGE, "gather: %lld rows of %d bytes exceed one launch", (long long)n, row_bytes);
+    TASER_HIP_TRY(hipGetLastError());
+    return TASER_OK;
+}
+
+extern "C" int taser_gather_features(const void* table, int64_t rows, int32_t row_bytes,
+                                     int64_t pitch_bytes, const int32_t* ids, int64_t n, void* out,
+                                     void* hip_stream) {
+    if (n < 0 || rows < 0) return taser_fail(TASER_E_ARG, "gather_features: negative size");
+    if (row_bytes <= 0 || (row_bytes & 1)) return taser_fail(TASER_E_ARG, "gather_features: row_bytes = %d must be positive and even", row_bytes);
+    if (pitch_bytes < row_bytes || (pitch_bytes & 1)) return taser_fail(TASER_E_ARG, "gather_features: pitch_bytes = %lld must be even and >= row_bytes", (long long)pitch_bytes);
+    if (n == 0) return TASER_OK;
+    if (!ids || !out) return taser_fail(TASER_E_ARG, "gather_features: null ids or out");
+    if (!table && rows > 0) return taser_fail(TASER_E_ARG, "gather_features: null table");
+    if (((uintptr_t)out & 1) || ((uintptr_t)table & 1)) return taser_fail(TASER_E_ARG, "gather_features: table and out must be 2-byte aligned");
+    return taser_launch_gather(table, rows, row_bytes, pitch_bytes, ids, n, out, (hipStream_t)hip_stream);
+}

@@ -1,0 +1,404 @@
+// taser_tcsr_build: the T-CSR of TASER (arXiv 2402.05396, Sec. 3.3): every
+// node's outgoing entries contiguous and ordered by timestamp, ties by input
+// position. Built on the device by a stable least-significant-digit radix
+// sort over the composite key (node, ts):
+//   * digits of the timestamp first (only those bytes in which the timestamps
+//     actually differ, and none at all when the input is already time-sorted,
+//     which is how event streams arrive), then the digits of the node id;
+//   * one pass = per-block digit histogram -> exclusive scan over the
+//     (digit, block) counters -> stable scatter. Inside a block the stable rank
+//     of an item among equal digits comes from wave ballots (which lanes hold
+//     my digit, how many of them are below me) plus per-wave running counters
+//     in LDS, so no atomics decide an output position;
+//   * the 16-byte record {ts, nbr, eid} the sampler reads travels with the key,
+//     so the last pass leaves the final layout in place;
+//   * indptr is read off the sorted node column (no atomics, no histogram).
+#include <new>
+#include <vector>
+
+#include "taser_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr int kItems = 16;                         // items per thread
+constexpr int kTile = kThreads * kItems;           // items per block
+constexpr int kBins = 256;                         // 8-bit digits
+
+struct DigitSpec {
+    int from_ts;      // 1: digit of the (sign-biased) timestamp, 0: digit of the node id
+    int shift;
+    uint32_t mask;
+};
+
+__device__ __forceinline__ uint64_t biased(int64_t ts) { return (uint64_t)ts ^ 0x8000000000000000ull; }
+
+__device__ __forceinline__ uint32_t digit_at(const TaserRec* rec, const int32_t* key, int64_t i, DigitSpec d) {
+    if (d.from_ts) return (uint32_t)(biased(rec[i].ts) >> d.shift) & d.mask;
+    return ((uint32_t)key[i] >> d.shift) & d.mask;
+}
+
+// Item r of lane `lane` of wave `wave` inside a tile: rows of 64 consecutive
+// items per wave, so loads are coalesced and index order = (wave, row, lane).
+__device__ __forceinline__ int64_t item_index(int64_t tile0, int wave, int r, int lane) {
+    return tile0 + (int64_t)wave * (kWave * kItems) + r * kWave + lane;
+}
+
+// info[0] != 0: a node id outside [0, num_nodes); info[1] != 0: timestamps not
+// non-decreasing in input order; info[2] / info[3]: OR / AND of the biased
+// timestamps (bytes in which they agree need no sorting pass).
+__global__ __launch_bounds__(kThreads) void inspect_kernel(const int32_t* __restrict__ src,
+                                                           const int64_t* __restrict__ ts, int64_t n,
+                                                           int32_t num_nodes, unsigned long long* info) {
+    unsigned long long any_or = 0, all_and = ~0ull;
+    int bad = 0, unsorted = 0;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kThreads) {
+        const int32_t s = src[i];
+        bad |= (s < 0 || s >= num_nodes);
+        const int64_t t = ts[i];
+        if (i + 1 < n) unsorted |= (ts[i + 1] < t);
+        any_or |= biased(t);
+        all_and &= biased(t);
+    }
+    for (int d = 1; d < kWave; d <<= 1) {
+        any_or |= __shfl_xor(any_or, d, kWave);
+        all_and &= __shfl_xor(all_and, d, kWave);
+    }
+    const unsigned long long any_bad = __ballot(bad), any_unsorted = __ballot(unsorted);
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+        if (any_bad) atomicOr(&info[0], 1ull);
+        if (any_unsorted) atomicOr(&info[1], 1ull);
+        atomicOr(&info[2], any_or);
+        atomicAnd(&info[3], all_and);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void pack_kernel(const int32_t* __restrict__ src,
+                                                        const int32_t* __restrict__ dst,
+                                                        const int64_t* __restrict__ ts,
+                                                        const int32_t* __restrict__ eid, int64_t n,
+                                                        TaserRec* __restrict__ rec, int32_t* __restrict__ key) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n) return;
+    TaserRec r;
+    r.ts = ts[i];
+    r.nbr = dst[i];
+    r.eid = eid ? eid[i] : (int32_t)i;
+    rec[i] = r;
+    key[i] = src[i];
+}
+
+// hist[bin * num_blocks + block] = items of this block's tile whose digit is bin.
+__global__ __launch_bounds__(kThreads) void radix_hist_kernel(const TaserRec* __restrict__ rec,
+                                                              const int32_t* __restrict__ key, int64_t n,
+                                                              DigitSpec d, uint32_t* __restrict__ hist,
+                                                              uint32_t num_blocks) {
+    __shared__ uint32_t bins[kBins];
+    bins[threadIdx.x] = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int64_t tile0 = (int64_t)blockIdx.x * kTile;
+#pragma unroll 4
+    for (int r = 0; r < kItems; ++r) {
+        const int64_t i = item_index(tile0, wave, r, lane);
+        if (i < n) atomicAdd(&bins[digit_at(rec, key, i, d)], 1u);
+    }
+    __syncthreads();
+    hist[(size_t)threadIdx.x * num_blocks + blockIdx.x] = bins[threadIdx.x];
+}
+
+// ---- exclusive scan of a uint32 array (total < 2^31), three kernels --------
+constexpr int kScanItems = 16;
+constexpr int kScanChunk = kThreads * kScanItems;
+
+// Exclusive scan of one value per thread across the block; returns the prefix
+// and leaves the block total in *total (valid for all threads).
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t* total) {
+    __shared__ uint32_t wave_sum[kWaves];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    uint32_t inc = x;
+    for (int d = 1; d < kWave; d <<= 1) {
+        const uint32_t y = __shfl_up(inc, d, kWave);
+        if (lane >= d) inc += y;
+    }
+    __syncthreads();                      // wave_sum may still be read from a previous call
+    if (lane == kWave - 1) wave_sum[wave] = inc;
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+    for (int w = 0; w < kWaves; ++w) {
+        const uint32_t s = wave_sum[w];
+        if (w < wave) before += s;
+        all += s;
+    }
+    *total = all;
+    return before + inc - x;
+}
+
+__global__ __launch_bounds__(kThreads) void scan_reduce_kernel(const uint32_t* __restrict__ a, int64_t n,
+                                                               uint32_t* __restrict__ partial) {
+    const int64_t base = (int64_t)blockIdx.x * kScanChunk + (int64_t)threadIdx.x * kScanItems;
+    uint32_t s = 0;
+    for (int j = 0; j < kScanItems; ++j)
+        if (base + j < n) s += a[base + j];
+    uint32_t total;
+    block_exclusive_scan(s, &total);
+    if (threadIdx.x == 0) partial[blockIdx.x] = total;
+}
+
+// One block: partial[] becomes its own exclusive scan.
+__global__ __launch_bounds__(kThreads) void scan_partials_kernel(uint32_t* partial, int64_t count) {
+    uint32_t carry = 0;
+    for (int64_t base = 0; base < count; base += kThreads) {
+        const int64_t i = base + threadIdx.x;
+        const uint32_t x = i < count ? partial[i] : 0;
+        uint32_t total;
+        const uint32_t ex = block_exclusive_scan(x, &total);
+        if (i < count) partial[i] = carry + ex;
+        carry += total;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void scan_apply_kernel(uint32_t* __restrict__ a, int64_t n,
+                                                              const uint32_t* __restrict__ partial) {
+    const int64_t base = (int64_t)blockIdx.x * kScanChunk + (int64_t)threadIdx.x * kScanItems;
+    uint32_t v[kScanItems];
+    uint32_t s = 0;
+    for (int j = 0; j < kScanItems; ++j) {
+        v[j] = base + j < n ? a[base + j] : 0;
+        s += v[j];
+    }
+    uint32_t total;
+    uint32_t run = partial[blockIdx.x] + block_exclusive_scan(s, &total);
+    for (int j = 0; j < kScanItems; ++j) {
+        if (base + j < n) a[base + j] = run;
+        run += v[j];
+    }
+}
+
+// Stable scatter of one tile. offs = the scanned histogram: offs[bin*num_blocks
+// + block] is where this block's first item with digit `bin` goes.
+__global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
+    const TaserRec* __restrict__ rec_in, const int32_t* __restrict__ key_in, int64_t n, DigitSpec d,
+    const uint32_t* __restrict__ offs, uint32_t num_blocks, TaserRec* __restrict__ rec_out,
+    int32_t* __restrict__ key_out) {
+    __shared__ uint32_t wave_count[kWaves][kBins];   // items of each wave per digit, then exclusive over waves
+    __shared__ uint32_t block_base[kBins];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int64_t tile0 = (int64_t)blockIdx.x * kTile;
+    for (int w = 0; w < kWaves; ++w) wave_count[w][threadIdx.x] = 0;
+    block_base[threadIdx.x] = offs[(size_t)threadIdx.x * num_blocks + blockIdx.x];
+    __syncthreads();
+
+    uint32_t digit[kItems], rank[kItems];
+    const uint64_t below = ((uint64_t)1 << lane) - 1;
+#pragma unroll
+    for (int r = 0; r < kItems; ++r) {
+        const int64_t i = item_index(tile0, wave, r, lane);
+        const bool valid = i < n;
+        const uint32_t dg = valid ? digit_at(rec_in, key_in, i, d) : 0u;
+        // lanes of this row that hold the same digit as me
+        uint64_t same = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const uint64_t has = __ballot(valid && ((dg >> b) & 1u));
+            same &= ((dg >> b) & 1u) ? has : ~has;
+        }
+        const uint32_t before_me = (uint32_t)__popcll(same & below);
+        uint32_t seen = 0;
+        if (valid) seen = wave_count[wave][dg];            // equal for all lanes of a digit
+        if (valid && before_me == 0) wave_count[wave][dg] = seen + (uint32_t)__popcll(same);
+        digit[r] = dg;
+        rank[r] = seen + before_me;
+        __builtin_amdgcn_wave_barrier();   // keep the LDS counter update of row r ahead of row r+1's read
+    }
+    __syncthreads();
+    {   // per digit: exclusive prefix of the wave counts over the waves
+        uint32_t run = 0;
+        for (int w = 0; w < kWaves; ++w) {
+            const uint32_t c = wave_count[w][threadIdx.x];
+            wave_count[w][threadIdx.x] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kItems; ++r) {
+        const int64_t i = item_index(tile0, wave, r, lane);
+        if (i < n) {
+            const uint32_t to = block_base[digit[r]] + wave_count[wave][digit[r]] + rank[r];
+            rec_out[to] = rec_in[i];
+            key_out[to] = key_in[i];
+        }
+    }
+}
+
+// indptr[v] = first position whose node id is >= v, from the sorted node column.
+__global__ __launch_bounds__(kThreads) void indptr_kernel(const int32_t* __restrict__ key, int64_t n,
+                                                          int32_t num_nodes, int64_t* __restrict__ indptr) {
+    const int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (p > n) return;
+    const int32_t prev = p > 0 ? key[p - 1] : -1;
+    const int32_t cur = p < n ? key[p] : num_nodes;
+    for (int32_t v = prev + 1; v <= cur; ++v) indptr[v] = p;
+}
+
+__global__ __launch_bounds__(kThreads) void unpack_kernel(const TaserRec* __restrict__ rec, int64_t n,
+                                                          int32_t* __restrict__ nbr, int64_t* __restrict__ ts,
+                                                          int32_t* __restrict__ eid) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n) return;
+    const TaserRec r = rec[i];
+    if (nbr) nbr[i] = r.nbr;
+    if (ts) ts[i] = r.ts;
+    if (eid) eid[i] = r.eid;
+}
+
+// Device allocation released at scope exit unless taken over.
+struct DevBuf {
+    void* p = nullptr;
+    ~DevBuf() { if (p) (void)hipFree(p); }
+    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 1); }
+    template <typename T> T* as() const { return static_cast<T*>(p); }
+    template <typename T> T* release() { T* t = static_cast<T*>(p); p = nullptr; return t; }
+};
+
+inline unsigned blocks_for(int64_t n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
+
+}  // namespace
+
+extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const int64_t* ts,
+                                const int32_t* eid, int64_t num_entries, int32_t num_nodes,
+                                uint32_t flags, void* hip_stream, taser_tcsr** out) {
+    if (!out) return taser_fail(TASER_E_ARG, "tcsr_build: null out");
+    *out = nullptr;
+    if (num_entries < 0 || num_entries >= 0x7fffffffLL) return taser_fail(TASER_E_RANGE, "tcsr_build: num_entries = %lld outside [0, 2^31 - 1)", (long long)num_entries);
+    if (num_nodes < 1 || num_nodes == 0x7fffffff) return taser_fail(TASER_E_RANGE, "tcsr_build: num_nodes = %d outside [1, 2^31 - 1)", num_nodes);
+    if (num_entries > 0 && (!src || !dst || !ts)) return taser_fail(TASER_E_ARG, "tcsr_build: null src/dst/ts");
+    if (flags & ~(uint32_t)TASER_INPUT_ON_DEVICE) return taser_fail(TASER_E_ARG, "tcsr_build: unknown flags 0x%x", flags);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const int64_t n = num_entries;
+
+    // ---- inputs in device memory
+    DevBuf in_src, in_dst, in_ts, in_eid;
+    if (!(flags & TASER_INPUT_ON_DEVICE) && n > 0) {
+        TASER_HIP_TRY(in_src.alloc(n * sizeof(int32_t)));
+        TASER_HIP_TRY(in_dst.alloc(n * sizeof(int32_t)));
+        TASER_HIP_TRY(in_ts.alloc(n * sizeof(int64_t)));
+        TASER_HIP_TRY(hipMemcpyAsync(in_src.p, src, n * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+        TASER_HIP_TRY(hipMemcpyAsync(in_dst.p, dst, n * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+        TASER_HIP_TRY(hipMemcpyAsync(in_ts.p, ts, n * sizeof(int64_t), hipMemcpyHostToDevice, stream));
+        src = in_src.as<int32_t>();
+        dst = in_dst.as<int32_t>();
+        ts = in_ts.as<int64_t>();
+        if (eid) {
+            TASER_HIP_TRY(in_eid.alloc(n * sizeof(int32_t)));
+            TASER_HIP_TRY(hipMemcpyAsync(in_eid.p, eid, n * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+            eid = in_eid.as<int32_t>();
+        }
+    }
+
+    // ---- range check and sort plan
+    unsigned long long info[4] = {0, 0, 0, ~0ull};
+    if (n > 0) {
+        DevBuf d_info;
+        TASER_HIP_TRY(d_info.alloc(sizeof(info)));
+        TASER_HIP_TRY(hipMemcpyAsync(d_info.p, info, sizeof(info), hipMemcpyHostToDevice, stream));
+        unsigned grid = blocks_for(n, kThreads);
+        if (grid > 4096) grid = 4096;
+        hipLaunchKernelGGL(inspect_kernel, dim3(grid), dim3(kThreads), 0, stream, src, ts, n, num_nodes,
+                           d_info.as<unsigned long long>());
+        TASER_HIP_TRY(hipGetLastError());
+        TASER_HIP_TRY(hipMemcpyAsync(info, d_info.p, sizeof(info), hipMemcpyDeviceToHost, stream));
+        TASER_HIP_TRY(hipStreamSynchronize(stream));
+        if (info[0]) return taser_fail(TASER_E_RANGE, "tcsr_build: a src node id is outside [0, %d)", num_nodes);
+    }
+    std::vector<DigitSpec> passes;
+    if (info[1]) {
+        const unsigned long long differ = info[2] & ~info[3];
+        for (int b = 0; b < 8; ++b)
+            if ((differ >> (8 * b)) & 0xffull) passes.push_back(DigitSpec{1, 8 * b, 0xffu});
+    }
+    int node_bits = 0;
+    while (((int64_t)1 << node_bits) < (int64_t)num_nodes) ++node_bits;
+    for (int shift = 0; shift < node_bits; shift += 8) {
+        const int width = node_bits - shift < 8 ? node_bits - shift : 8;
+        passes.push_back(DigitSpec{0, shift, (1u << width) - 1u});
+    }
+
+    // ---- pack, then one stable pass per digit, ping-pong between two buffers
+    DevBuf rec_a, key_a, rec_b, key_b, hist, partial, indptr;
+    TASER_HIP_TRY(rec_a.alloc(n * sizeof(TaserRec)));
+    TASER_HIP_TRY(key_a.alloc(n * sizeof(int32_t)));
+    TASER_HIP_TRY(indptr.alloc(((size_t)num_nodes + 1) * sizeof(int64_t)));
+    const uint32_t num_blocks = blocks_for(n, kTile);
+    const int64_t hist_len = (int64_t)kBins * num_blocks;
+    const unsigned scan_blocks = blocks_for(hist_len, kScanChunk);
+    if (n > 0) {
+        hipLaunchKernelGGL(pack_kernel, dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, stream, src, dst, ts,
+                           eid, n, rec_a.as<TaserRec>(), key_a.as<int32_t>());
+        if (!passes.empty()) {
+            TASER_HIP_TRY(rec_b.alloc(n * sizeof(TaserRec)));
+            TASER_HIP_TRY(key_b.alloc(n * sizeof(int32_t)));
+            TASER_HIP_TRY(hist.alloc(hist_len * sizeof(uint32_t)));
+            TASER_HIP_TRY(partial.alloc((size_t)scan_blocks * sizeof(uint32_t)));
+        }
+        for (const DigitSpec& d : passes) {
+            hipLaunchKernelGGL(radix_hist_kernel, dim3(num_blocks), dim3(kThreads), 0, stream,
+                               rec_a.as<TaserRec>(), key_a.as<int32_t>(), n, d, hist.as<uint32_t>(), num_blocks);
+            hipLaunchKernelGGL(scan_reduce_kernel, dim3(scan_blocks), dim3(kThreads), 0, stream,
+                               hist.as<uint32_t>(), hist_len, partial.as<uint32_t>());
+            hipLaunchKernelGGL(scan_partials_kernel, dim3(1), dim3(kThreads), 0, stream, partial.as<uint32_t>(),
+                               (int64_t)scan_blocks);
+            hipLaunchKernelGGL(scan_apply_kernel, dim3(scan_blocks), dim3(kThreads), 0, stream,
+                               hist.as<uint32_t>(), hist_len, partial.as<uint32_t>());
+            hipLaunchKernelGGL(radix_scatter_kernel, dim3(num_blocks), dim3(kThreads), 0, stream,
+                               rec_a.as<TaserRec>(), key_a.as<int32_t>(), n, d, hist.as<uint32_t>(), num_blocks,
+                               rec_b.as<TaserRec>(), key_b.as<int32_t>());
+            void* t = rec_a.p; rec_a.p = rec_b.p; rec_b.p = t;
+            t = key_a.p; key_a.p = key_b.p; key_b.p = t;
+        }
+    }
+    hipLaunchKernelGGL(indptr_kernel, dim3(blocks_for(n + 1, kThreads)), dim3(kThreads), 0, stream,
+                       key_a.as<int32_t>(), n, num_nodes, indptr.as<int64_t>());
+    TASER_HIP_TRY(hipGetLastError());
+    TASER_HIP_TRY(hipStreamSynchronize(stream));
+
+    taser_tcsr* g = new (std::nothrow) taser_tcsr();
+    if (!g) return taser_fail(TASER_E_OOM, "tcsr_build: host allocation failed");
+    g->num_entries = n;
+    g->num_nodes = num_nodes;
+    g->indptr = indptr.release<int64_t>();
+    g->rec = rec_a.release<TaserRec>();
+    *out = g;
+    return TASER_OK;
+}
+
+extern "C" int taser_tcsr_size(const taser_tcsr* g, int64_t* num_entries, int32_t* num_nodes) {
+    if (!g) return taser_fail(TASER_E_ARG, "tcsr_size: null graph");
+    if (num_entries) *num_entries = g->num_entries;
+    if (num_nodes) *num_nodes = g->num_nodes;
+    return TASER_OK;
+}
+
+extern "C" int taser_tcsr_view(const taser_tcsr* g, int64_t* indptr, int32_t* nbr, int64_t* ts, int32_t* eid,
+                               void* hip_stream) {
+    if (!g) return taser_fail(TASER_E_ARG, "tcsr_view: null graph");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (indptr)
+        TASER_HIP_TRY(hipMemcpyAsync(indptr, g->indptr, ((size_t)g->num_nodes + 1) * sizeof(int64_t),
+                                     hipMemcpyDeviceToDevice, stream));
+    if ((nbr || ts || eid) && g->num_entries > 0) {
+        hipLaunchKernelGGL(unpack_kernel, dim3(blocks_for(g->num_entries, kThreads)), dim3(kThreads), 0, stream,
+                           g->rec, g->num_entries, nbr, ts, eid);
+        TASER_HIP_TRY(hipGetLastError());
+    }
+    return TASER_OK;
+}
+
+extern "C" void taser_tcsr_free(taser_tcsr* g) {
+    if (!g) return;
+    (void)hipFree(g->indptr);
+    (void)hipFree(g->rec);
+    delete g;
+}

@@ -1,0 +1,332 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by
+element, on seeded synthetic inputs. Bit-exact: everything on this path is
+integer/index/byte work."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2402_05396_amd as T
+from paper_2402_05396_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+THREADS = min(16, oracle.max_threads())
+FIELDS = ("nbr", "eid", "ts", "count")
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def build_both(src, dst, ts, eid, num_nodes, on_device=True):
+    g_ref = oracle.tcsr_build(src, dst, ts, eid, num_nodes, THREADS)
+    args = [torch.from_numpy(np.ascontiguousarray(x)) for x in (src, dst, ts, eid)]
+    if on_device:
+        args = [a.cuda() for a in args]
+    g = T.tcsr_build(*args, num_nodes)
+    return g, g_ref
+
+
+def assert_tcsr_equal(g, g_ref):
+    got = [x.cpu().numpy() for x in T.tcsr_view(g)]
+    for name, a, b in zip(("indptr", "nbr", "ts", "eid"), got, g_ref):
+        assert a.dtype == b.dtype and np.array_equal(a, b), name
+
+
+def assert_hops_equal(got, want):
+    assert len(got) == len(want)
+    for h, (a, b) in enumerate(zip(got, want)):
+        for f in FIELDS:
+            x = a[f].cpu().numpy()
+            assert x.shape == b[f].shape and np.array_equal(x, b[f]), f"hop {h} field {f}"
+
+
+def run_both(g, g_ref, roots, times, k, hops, policy, seed, m=0, weight=None):
+    want = oracle.sample_temporal(g_ref, roots, times, k, hops, policy, seed, m, weight, THREADS)
+    w_dev = None if weight is None else dev(weight.view(np.int32))
+    got = T.sample_temporal(g, dev(roots), dev(times), k, hops, policy, seed, m, w_dev)
+    torch.cuda.synchronize()
+    assert_hops_equal(got, want)
+    return got, want
+
+
+def check_gather(table_np, table_dev, ids_dev_2d, ids_np_2d):
+    want = oracle.gather(table_np, ids_np_2d.ravel(), threads=THREADS)
+    got = T.gather_features(table_dev, ids_dev_2d.reshape(-1), row_elems=table_np.shape[1])
+    torch.cuda.synchronize()
+    assert got.cpu().numpy().tobytes() == want.tobytes()
+
+
+# ----------------------------------------------------------------------------- the five workloads
+def test_c1_tiny_all_batches():
+    w = W.make(1)
+    g, g_ref = build_both(w.src, w.dst, w.ts, w.eid, w.num_nodes, on_device=False)
+    assert_tcsr_equal(g, g_ref)
+    table = dev(w.edge_feat)
+    for b, (roots, times) in enumerate(w.batches):
+        for policy in w.policies:
+            got, want = run_both(g, g_ref, roots, times, w.k, 1, policy, seed=42 + b)
+            check_gather(w.edge_feat, table, got[0]["eid"], want[0]["eid"])
+    assert sum(int((r >= 0).sum()) for r, _ in w.batches) == 6000
+
+
+def test_c2_one_hop_recent_and_uniform():
+    w = W.make(2)
+    g, g_ref = build_both(w.src, w.dst, w.ts, w.eid, w.num_nodes)
+    assert_tcsr_equal(g, g_ref)
+    table = dev(w.edge_feat)
+    assert len(w.batches) == 267 and w.batches[-1][0].shape[0] == 1200
+    for b in (0, 1, 2, 50, 133, 200, 265, 266):        # cold start ... ragged last batch
+        roots, times = w.batches[b]
+        for policy in w.policies:
+            got, want = run_both(g, g_ref, roots, times, w.k, 1, policy, seed=42)
+            check_gather(w.edge_feat, table, got[0]["eid"], want[0]["eid"])
+
+
+def test_c3_two_hop_uniform_fp16():
+    w = W.make(3, num_batches=3)
+    g, g_ref = build_both(w.src, w.dst, w.ts, w.eid, w.num_nodes)
+    assert_tcsr_equal(g, g_ref)
+    table = dev(w.edge_feat)
+    for roots, times in w.batches:
+        got, want = run_both(g, g_ref, roots, times, w.k, 2, W.UNIFORM, seed=42)
+        assert got[1]["nbr"].shape == (60000, 10)
+        for h in range(2):
+            check_gather(w.edge_feat, table, got[h]["eid"], want[h]["eid"])
+
+
+def test_c4_two_hop_weighted():
+    w = W.make(4, num_batches=2)
+    g, g_ref = build_both(w.src, w.dst, w.ts, w.eid, w.num_nodes)
+    assert_tcsr_equal(g, g_ref)
+    table = dev(w.edge_feat)
+    for roots, times in w.batches:
+        got, want = run_both(g, g_ref, roots, times, w.k, 2, W.WEIGHTED, seed=42, m=w.m, weight=w.edge_weight)
+        for h in range(2):
+            check_gather(w.edge_feat, table, got[h]["eid"], want[h]["eid"])
+
+
+def test_c5_scaled_two_hop_recent_with_cache():
+    """The GDELT-shaped workload at 2 M events (same node count, skew and tie density):
+    full element-wise parity of sampler, pitched procedural edge table gather and the
+    cached node-feature gather from pinned host memory."""
+    w = W.make(5, edges=2_000_000, num_batches=2, last=200_000)
+    g, g_ref = build_both(w.src, w.dst, w.ts, w.eid, w.num_nodes)
+    assert_tcsr_equal(g, g_ref)
+    pitch = 192                                                  # 384-byte rows for 372 bytes of data
+    table = W.procedural_table_torch(w.edge_seed, w.num_edges, w.edge_dim, torch.float16, pitch, "cuda")
+    node_host = torch.from_numpy(w.node_feat).pin_memory()
+    cap = int(w.cache_ratio * w.num_nodes)
+    hot = torch.from_numpy(np.ascontiguousarray(w.notes["hot_order"][:cap]))
+    cache = T.cache_init(node_host, cap, hot, staging_rows=w.num_nodes - cap)
+    for roots, times in w.batches:
+        got, want = run_both(g, g_ref, roots, times, w.k, 2, W.RECENT, seed=42)
+        for h in range(2):
+            eids = want[h]["eid"].ravel()
+            rows = W.procedural_rows(w.edge_seed, np.maximum(eids, 0), w.edge_dim, np.float16)
+            rows[eids < 0] = 0
+            out = T.gather_features(table, got[h]["eid"].reshape(-1), row_elems=w.edge_dim)
+            assert out.cpu().numpy().tobytes() == rows.tobytes()
+        ids_np = np.concatenate([roots, want[0]["nbr"].ravel(), want[1]["nbr"].ravel()])
+        ids = torch.cat([dev(roots), got[0]["nbr"].reshape(-1), got[1]["nbr"].reshape(-1)])
+        hm = torch.zeros(2, dtype=torch.int64, device="cuda")
+        out = T.cache_lookup(cache, ids, hit_miss=hm)
+        torch.cuda.synchronize()
+        assert out.cpu().numpy().tobytes() == oracle.gather(w.node_feat, ids_np, threads=THREADS).tobytes()
+        assert tuple(hm.tolist()) == oracle.cache_hits(hot.numpy(), w.num_nodes, ids_np)
+
+
+# ----------------------------------------------------------------------------- sampler edge cases
+def _graph(rng, n_nodes, n, span, sorted_ts=True, lo=0):
+    src = rng.integers(0, n_nodes, n).astype(np.int32)
+    dst = rng.integers(0, n_nodes, n).astype(np.int32)
+    ts = rng.integers(lo, lo + span, n).astype(np.int64)
+    if sorted_ts:
+        ts.sort()
+    eid = rng.permutation(n).astype(np.int32)
+    return src, dst, ts, eid
+
+
+@pytest.mark.parametrize("sorted_ts,lo,span", [(True, 0, 500), (False, 0, 500), (False, -(1 << 62), 1 << 40),
+                                              (False, -300, 70000), (True, 5, 1)])
+def test_tcsr_build_general_inputs(sorted_ts, lo, span):
+    """Unsorted timestamps (the timestamp digits must then be sorted too), negative and
+    huge timestamps, heavy ties, an empty node, host and device inputs, ragged tile."""
+    rng = np.random.default_rng(17)
+    n_nodes, n = 300, 3 * 4096 + 777
+    src, dst, ts, eid = _graph(rng, n_nodes, n, span, sorted_ts, lo)
+    src[src == 9] = 10
+    for on_device in (True, False):
+        g, g_ref = build_both(src, dst, ts, eid, n_nodes, on_device)
+        assert_tcsr_equal(g, g_ref)
+    g = T.tcsr_build(dev(src), dev(dst), dev(ts), None, n_nodes)            # eid defaults to the position
+    _, _, _, got_eid = T.tcsr_view(g)
+    ref = oracle.tcsr_build(src, dst, ts, np.arange(n, dtype=np.int32), n_nodes)
+    assert np.array_equal(got_eid.cpu().numpy(), ref[3])
+
+
+@pytest.mark.parametrize("n_nodes", [1, 2, 255, 257, 70000])
+def test_tcsr_build_node_count_digits(n_nodes):
+    rng = np.random.default_rng(n_nodes)
+    src, dst, ts, eid = _graph(rng, n_nodes, 20000, 1000)
+    g, g_ref = build_both(src, dst, ts, eid, n_nodes)
+    assert_tcsr_equal(g, g_ref)
+
+
+def test_tcsr_build_empty_and_rejects_bad_ids():
+    z32, z64 = torch.zeros(0, dtype=torch.int32), torch.zeros(0, dtype=torch.int64)
+    g = T.tcsr_build(z32.cuda(), z32.cuda(), z64.cuda(), None, 5)
+    indptr, nbr, _, _ = T.tcsr_view(g)
+    assert indptr.tolist() == [0] * 6 and nbr.numel() == 0
+    out = T.sample_temporal(g, dev(np.array([0, 4], np.int32)), dev(np.array([5, 5], np.int64)), 3, 2, T.UNIFORM, 1)
+    assert out[0]["count"].tolist() == [0, 0] and out[1]["nbr"].shape == (6, 3) and int(out[1]["nbr"].max()) == -1
+    with pytest.raises(T.TaserError) as e:
+        T.tcsr_build(dev(np.array([0, 5], np.int32)), dev(np.array([1, 1], np.int32)), dev(np.array([0, 1], np.int64)),
+                     None, 5)
+    assert e.value.code == -2
+
+
+@pytest.mark.parametrize("policy", [T.RECENT, T.UNIFORM, T.WEIGHTED])
+@pytest.mark.parametrize("k,m", [(1, 2), (10, 25), (32, 64), (64, 64), (7, 5)])
+def test_sampler_shapes_and_policies(policy, k, m):
+    """Small and maximal k / m, three hops, degree mix from empty lists to thousands."""
+    rng = np.random.default_rng(100 * k + m)
+    n_nodes, n = 60, 30000
+    src, dst, ts, eid = _graph(rng, n_nodes, n, 4000)
+    src = np.minimum(src, rng.integers(0, n_nodes, n)).astype(np.int32)     # skewed degrees
+    src[src == 7] = 8
+    g, g_ref = build_both(src, dst, ts, eid, n_nodes)
+    weight = rng.integers(1, 1 << 16, n).astype(np.uint32)
+    roots = rng.integers(0, n_nodes, 333).astype(np.int32)
+    roots[::50] = -1
+    times = rng.integers(-5, 4100, 333).astype(np.int64)
+    hops = 3 if k <= 7 else (2 if k <= 10 else 1)
+    run_both(g, g_ref, roots, times, k, hops, policy, seed=0xABCDEF0123456789, m=m, weight=weight)
+
+
+@pytest.mark.parametrize("policy", [T.RECENT, T.UNIFORM, T.WEIGHTED])
+def test_sampler_long_lists_and_ties(policy):
+    """Lists long enough for several rounds of the wave-wide search (64^3 < 300 k), query
+    times on, between and outside the timestamps, and long runs of equal timestamps."""
+    rng = np.random.default_rng(4)
+    n = 300_000
+    src = np.zeros(n, np.int32)
+    src[-5000:] = 1
+    src[-70:-64] = 2
+    dst = rng.integers(0, 4, n).astype(np.int32)
+    ts = np.sort(rng.integers(0, 3000, n)).astype(np.int64) * 7          # ~100 equal timestamps in a row
+    eid = np.arange(n, dtype=np.int32)
+    g, g_ref = build_both(src, dst, ts, eid, 4)
+    weight = rng.integers(1, 1 << 16, n).astype(np.uint32)
+    times = np.concatenate([np.arange(-2, 90), rng.integers(0, 21010, 1500), [21000, 20993, 20994, 1 << 62, -(1 << 62)]])
+    roots = rng.integers(0, 4, times.shape[0]).astype(np.int32)
+    roots[:92] = 0
+    run_both(g, g_ref, roots, times.astype(np.int64), 10, 2, policy, seed=7, m=25, weight=weight)
+
+
+def test_sampler_weight_extremes():
+    """uint32 weights up to 2^32 - 1: the running sums need 64 bits."""
+    rng = np.random.default_rng(12)
+    src, dst, ts, eid = _graph(rng, 5, 4000, 9000)
+    g, g_ref = build_both(src, dst, ts, eid, 5)
+    weight = rng.integers(1, 1 << 32, 4000, dtype=np.uint64).astype(np.uint32)
+    weight[::3] = 0xFFFFFFFF
+    weight[1::5] = 1
+    roots = rng.integers(0, 5, 500).astype(np.int32)
+    times = rng.integers(0, 9000, 500).astype(np.int64)
+    run_both(g, g_ref, roots, times, 16, 1, T.WEIGHTED, seed=3, m=64, weight=weight)
+
+
+def test_sampler_is_deterministic_and_independent_of_batch_split():
+    w = W.make(1)
+    g, _ = build_both(w.src, w.dst, w.ts, w.eid, w.num_nodes)
+    roots, times = w.batches[9]
+    a = T.sample_temporal(g, dev(roots), dev(times), 10, 2, T.UNIFORM, 5)
+    b = T.sample_temporal(g, dev(roots), dev(times), 10, 2, T.UNIFORM, 5)
+    for h in range(2):
+        for f in FIELDS:
+            assert torch.equal(a[h][f], b[h][f])
+    c = T.sample_temporal(g, dev(roots), dev(times), 10, 1, T.UNIFORM, 6)
+    assert not torch.equal(a[0]["eid"], c[0]["eid"])                  # the seed matters
+    assert torch.equal(a[0]["count"], c[0]["count"])
+
+
+# ----------------------------------------------------------------------------- gather edge cases
+@pytest.mark.parametrize("dtype,dim,pad,offset", [
+    (np.float32, 16, 0, 0),      # 64-byte rows, 16-byte vectors
+    (np.float32, 172, 0, 0),     # 688 bytes
+    (np.float16, 172, 0, 0),     # 344 bytes: 8-byte vectors
+    (np.float16, 186, 0, 0),     # 372 bytes: 4-byte vectors, unpadded
+    (np.float16, 186, 6, 0),     # 372 bytes at a 384-byte pitch
+    (np.float32, 413, 0, 0),     # 1652 bytes
+    (np.float16, 7, 0, 0),       # 14 bytes: 2-byte path
+    (np.float16, 9, 3, 1),       # odd everything, table view starting 2 bytes into an allocation
+    (np.float32, 1, 0, 0),       # 4-byte rows
+    (np.float32, 300, 20, 4),    # 1200 bytes, 16-byte aligned data inside a wider pitch
+])
+def test_gather_alignments(dtype, dim, pad, offset):
+    rng = np.random.default_rng(dim)
+    rows = 3000
+    full = rng.standard_normal((rows, dim + pad + offset)).astype(dtype)
+    table = full[:, offset:offset + dim]
+    full_dev = dev(full)
+    table_dev = full_dev[:, offset:offset + dim]
+    for n in (0, 1, 63, 1025, 7777):
+        ids = rng.integers(0, rows, n).astype(np.int32)
+        ids[::11] = -1
+        got = T.gather_features(table_dev, dev(ids))
+        assert got.shape == (n, dim)
+        assert got.cpu().numpy().tobytes() == oracle.gather(table, ids).tobytes()
+
+
+def test_gather_out_of_range_ids_give_zero_rows():
+    table = torch.arange(40, dtype=torch.float32, device="cuda").reshape(10, 4)
+    out = T.gather_features(table, dev(np.array([3, 10, 2 ** 31 - 1, -7, 9], np.int32)))
+    assert out.tolist() == [[12, 13, 14, 15], [0] * 4, [0] * 4, [0] * 4, [36, 37, 38, 39]]
+
+
+# ----------------------------------------------------------------------------- cache
+@pytest.mark.parametrize("cap_frac,staging", [(0.0, 0), (0.0, 10000), (0.2, 0), (0.2, 16), (0.2, 5000), (1.0, 0)])
+def test_cache_serves_identical_bytes_whatever_is_resident(cap_frac, staging):
+    rng = np.random.default_rng(77)
+    rows, dim = 5000, 413
+    host = torch.from_numpy(rng.standard_normal((rows, dim)).astype(np.float32)).pin_memory()
+    cap = int(cap_frac * rows)
+    ids = np.minimum(rng.zipf(1.3, 60000) - 1, rows - 1).astype(np.int32)
+    ids[::97] = -1
+    want = oracle.gather(host.numpy(), ids, threads=THREADS)
+    for residents in (None, torch.from_numpy(rng.permutation(rows)[:cap].astype(np.int32))):
+        c = T.cache_init(host, cap, residents, seed=9, staging_rows=staging)
+        res = T.cache_residents(c).numpy()
+        if residents is None:
+            assert np.array_equal(res, oracle.cache_random_residents(rows, cap, 9))
+        else:
+            assert np.array_equal(res, residents.numpy())
+        hm = torch.zeros(2, dtype=torch.int64, device="cuda")
+        for _ in range(2):                                            # the per-call staging state is reset
+            out = T.cache_lookup(c, dev(ids), hit_miss=hm)
+            torch.cuda.synchronize()
+            assert out.cpu().numpy().tobytes() == want.tobytes()
+        h, m = oracle.cache_hits(res, rows, ids)
+        assert tuple(hm.tolist()) == (2 * h, 2 * m)
+        out = T.cache_lookup(c, dev(ids[:100]))                       # shrinking n, no counters
+        assert out.cpu().numpy().tobytes() == want[:100].tobytes()
+        T.cache_free(c)
+
+
+def test_cache_rejects_unpinned_and_bad_residents():
+    host = torch.zeros((100, 8), dtype=torch.float32)
+    with pytest.raises(T.TaserError) as e:
+        T.cache_init(host, 10)
+    assert e.value.code == -1 and "page-locked" in str(e.value)
+    pinned = host.pin_memory()
+    with pytest.raises(T.TaserError) as e:
+        T.cache_init(pinned, 2, torch.tensor([5, 5], dtype=torch.int32))
+    assert e.value.code == -2
+    # an error from the library leaves HIP usable
+    c = T.cache_init(pinned, 2, torch.tensor([5, 6], dtype=torch.int32))
+    assert T.cache_lookup(c, dev(np.array([5, 1], np.int32))).abs().sum().item() == 0

@@ -1,0 +1,90 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, and rejects bad arguments before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2402_05396_amd as T
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "taser.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(taser_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert len(names) >= 10
+    lib = T.lib()
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in taser.h but not exported"
+    assert set(T.EXPORTS) == set(names)
+
+
+def test_binding_mirrors_entry_points():
+    for n in T.EXPORTS:
+        assert hasattr(T, n[len("taser_"):]), n
+
+
+def test_argument_errors_are_reported_without_a_gpu():
+    lib = T.lib()
+    h = ctypes.c_void_p()
+    one = ctypes.c_void_p(8)      # never dereferenced: validation fails first
+    E_ARG, E_RANGE = -1, -2
+    assert lib.taser_tcsr_build(None, None, None, None, 4, 3, 0, None, ctypes.byref(h)) == E_ARG
+    assert "null" in T.last_error()
+    assert lib.taser_tcsr_build(one, one, one, None, -1, 3, 0, None, ctypes.byref(h)) == E_RANGE
+    assert lib.taser_tcsr_build(one, one, one, None, 2 ** 31, 3, 0, None, ctypes.byref(h)) == E_RANGE
+    assert lib.taser_tcsr_build(one, one, one, None, 4, 0, 0, None, ctypes.byref(h)) == E_RANGE
+    assert lib.taser_tcsr_build(one, one, one, None, 4, 3, 64, None, ctypes.byref(h)) == E_ARG
+    assert lib.taser_tcsr_build(one, one, one, None, 4, 3, 0, None, None) == E_ARG
+    assert lib.taser_tcsr_size(None, None, None) == E_ARG
+    assert lib.taser_tcsr_view(None, None, None, None, None, None) == E_ARG
+
+    out = (T._HopOut * 1)()
+    assert lib.taser_sample_temporal(None, one, one, 1, 10, 1, 0, 0, 0, None, out, None) == E_ARG
+    g = one                       # the handle is not dereferenced before validation ends
+    assert lib.taser_sample_temporal(g, one, one, 1, 0, 1, 0, 0, 0, None, out, None) == E_RANGE
+    assert lib.taser_sample_temporal(g, one, one, 1, 65, 1, 0, 0, 0, None, out, None) == E_RANGE
+    assert lib.taser_sample_temporal(g, one, one, 1, 10, 0, 0, 0, 0, None, out, None) == E_RANGE
+    assert lib.taser_sample_temporal(g, one, one, 1, 10, 4, 0, 0, 0, None, out, None) == E_RANGE
+    assert lib.taser_sample_temporal(g, one, one, 1, 10, 1, 7, 0, 0, None, out, None) == E_ARG
+    assert lib.taser_sample_temporal(g, one, one, 1, 10, 1, 2, 0, 0, one, out, None) == E_RANGE   # m = 0
+    assert lib.taser_sample_temporal(g, one, one, 1, 10, 1, 2, 0, 25, None, out, None) == E_ARG   # no weights
+    assert lib.taser_sample_temporal(g, one, one, 1, 10, 1, 0, 0, 0, None, out, None) == E_ARG    # null out buffers
+    assert lib.taser_sample_temporal(g, one, one, -1, 10, 1, 0, 0, 0, None, out, None) == E_ARG
+    assert lib.taser_sample_temporal(g, one, one, 2 ** 28, 10, 1, 0, 0, 0, None, out, None) == E_ARG  # null buffers first
+    big = (T._HopOut * 1)()
+    for f in ("nbr", "eid", "ts", "count"):
+        setattr(big[0], f, 8)
+    assert lib.taser_sample_temporal(g, one, one, 2 ** 28, 10, 1, 0, 0, 0, None, big, None) == E_RANGE
+
+    assert lib.taser_gather_features(one, 4, 0, 16, one, 1, one, None) == E_ARG
+    assert lib.taser_gather_features(one, 4, 15, 16, one, 1, one, None) == E_ARG
+    assert lib.taser_gather_features(one, 4, 16, 8, one, 1, one, None) == E_ARG
+    assert lib.taser_gather_features(one, 4, 16, 16, None, 1, one, None) == E_ARG
+    assert lib.taser_gather_features(one, 4, 16, 16, one, -1, one, None) == E_ARG
+    assert lib.taser_gather_features(one, 4, 16, 16, one, 0, one, None) == 0      # nothing to do
+
+    c = ctypes.c_void_p()
+    assert lib.taser_cache_init(None, 4, 16, 16, 1, None, 0, 0, None, ctypes.byref(c)) == E_ARG
+    assert lib.taser_cache_init(one, 0, 16, 16, 0, None, 0, 0, None, ctypes.byref(c)) == E_RANGE
+    assert lib.taser_cache_init(one, 4, 18, 20, 1, None, 0, 0, None, ctypes.byref(c)) == E_ARG
+    assert lib.taser_cache_init(one, 4, 16, 16, 5, None, 0, 0, None, ctypes.byref(c)) == E_RANGE
+    assert lib.taser_cache_init(one, 4, 16, 16, 1, None, 0, -1, None, ctypes.byref(c)) == E_RANGE
+    assert lib.taser_cache_lookup(None, one, 1, one, None, None) == E_ARG
+    assert lib.taser_cache_residents(None, None) == E_ARG
+    lib.taser_tcsr_free(None)
+    lib.taser_cache_free(None)
+
+
+def test_binding_fails_loudly_when_the_library_is_missing(monkeypatch):
+    monkeypatch.setattr(T, "_lib", None)
+    monkeypatch.setattr(T, "LIB_PATH", os.path.join(ROOT, "does_not_exist.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        T.lib()
