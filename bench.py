@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the mini-batch generation hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic roots:
+temporal sampling over 2 hops -> edge-feature gather of every sampled edge ->
+node-feature gather (through the device cache) of every root and sampled
+neighbor. Inputs (graph, tables, root arrays) are resident in device memory
+before the timed region. Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+EDGE_PITCH_ELEMS = {186: 192}   # rows padded to whole 128-byte lines where the width is awkward
+
+# HBM traffic per launch of the dominant kernel measured offline with
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=5, choices=[3, 4, 5])
+    ap.add_argument("--edges", type=int, default=None, help="override the event count (smaller = not the named workload)")
+    ap.add_argument("--cpu-roots", type=int, default=6000, help="roots of batch 0 the CPU oracle is timed on (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (the path has no cross-GPU part); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2402_05396_amd as T
+    from paper_2402_05396_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    T.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    t0 = time.time()
+    kw = {} if args.edges is None else {"edges": args.edges}
+    w = W.make(args.config, **kw)
+    policy = w.policies[0]
+    log(f"workload {w.name}: {w.num_nodes} nodes, {w.num_edges} events, generated in {time.time() - t0:.1f}s")
+
+    # ------------------------------------------------------------------ resident inputs
+    d_src, d_dst, d_ts, d_eid = (torch.from_numpy(x).to(dev) for x in (w.src, w.dst, w.ts, w.eid))
+    torch.cuda.synchronize()
+    T.profile_begin()
+    t0 = time.time()
+    g = T.tcsr_build(d_src, d_dst, d_ts, d_eid, w.num_nodes)
+    torch.cuda.synchronize()
+    build_wall_ms = (time.time() - t0) * 1e3
+    build_kernels = T.profile_end()
+    build_dev_ms = sum(ms for _, ms in build_kernels.values())
+    del d_src, d_dst, d_ts, d_eid
+    log(f"tcsr_build: {build_wall_ms:.1f} ms wall, {build_dev_ms:.2f} ms in kernels")
+
+    edge_dtype = torch.float16 if w.edge_dtype == "float16" else torch.float32
+    pitch = EDGE_PITCH_ELEMS.get(w.edge_dim, w.edge_dim)
+    if w.edge_feat is None:
+        edge_table = W.procedural_table_torch(w.edge_seed, w.num_edges, w.edge_dim, edge_dtype, pitch, dev)
+    else:
+        edge_table = torch.zeros((w.num_edges, pitch), dtype=edge_dtype, device=dev)
+        edge_table[:, :w.edge_dim] = torch.from_numpy(w.edge_feat).to(dev)
+    edge_table = edge_table[:, :w.edge_dim]
+    weight = None if w.edge_weight is None else torch.from_numpy(w.edge_weight.view(np.int32)).to(dev)
+
+    cache = None
+    if w.node_feat is not None:
+        node_host = torch.from_numpy(w.node_feat).pin_memory()
+        cap = int(w.cache_ratio * w.num_nodes)
+        hot = torch.from_numpy(np.ascontiguousarray(w.notes["hot_order"][:cap]))
+        cache = T.cache_init(node_host, cap, hot, staging_rows=w.num_nodes - cap)
+    torch.cuda.synchronize()
+    log(f"tables resident after {time.time() - t0:.1f}s")
+
+    k, hops = w.k, w.hops
+    R = w.batches[0][0].shape[0]
+    n_slots = [R * k ** (h + 1) for h in range(hops)]            # sampled slots per hop
+    n_ids = R + sum(n_slots)
+    batches = []
+    for roots, times in w.batches:
+        ids = torch.empty(n_ids, dtype=torch.int32, device=dev)   # [roots | nbr hop 0 | nbr hop 1]
+        ids[:R] = torch.from_numpy(roots).to(dev)
+        eids = torch.empty(sum(n_slots), dtype=torch.int32, device=dev)
+        out, at_n, at_e, r = [], R, 0, R
+        for h in range(hops):
+            out.append(dict(nbr=ids[at_n:at_n + n_slots[h]], eid=eids[at_e:at_e + n_slots[h]],
+                            ts=torch.empty(n_slots[h], dtype=torch.int64, device=dev),
+                            count=torch.empty(r, dtype=torch.int32, device=dev)))
+            at_n += n_slots[h]
+            at_e += n_slots[h]
+            r *= k
+        batches.append(dict(roots=ids[:R], times=torch.from_numpy(times).to(dev), ids=ids, eids=eids, out=out))
+    edge_out = torch.empty((sum(n_slots), w.edge_dim), dtype=edge_dtype, device=dev)
+    node_out = None if cache is None else torch.empty((n_ids, w.node_feat.shape[1]), dtype=torch.float32, device=dev)
+    hit_miss = torch.zeros(2, dtype=torch.int64, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(b):
+        T.sample_temporal(g, b["roots"], b["times"], k, hops, policy, 42, w.m, weight, out=b["out"], stream=stream)
+        T.gather_features(edge_table, b["eids"], out=edge_out, stream=stream)
+        if cache is not None:
+            T.cache_lookup(cache, b["ids"], out=node_out, hit_miss=hit_miss, stream=stream)
+
+    for i in range(args.warmup):
+        step(batches[i % len(batches)])
+    torch.cuda.synchronize()
+    hit_miss.zero_()
+    torch.cuda.synchronize()
+
+    # ------------------------------------------------------------------ timed region
+    T.profile_begin()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(batches[i % len(batches)])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kernels = T.profile_end()
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    # ------------------------------------------------------------------ accounting
+    used = [batches[i % len(batches)] for i in range(args.steps)]
+    neighbors = sum(int(sum(int(o["count"].sum()) for o in b["out"])) for b in used)
+    edge_rb = w.edge_dim * edge_table.element_size()
+    node_rb = 0 if cache is None else w.node_feat.shape[1] * 4
+    edge_bytes = sum(n_slots) * (2 * edge_rb + 4)                 # row read + row written + id
+    node_bytes = n_ids * (2 * node_rb + 4) if cache is not None else 0
+    gather_bytes_per_step = edge_bytes + node_bytes
+    value = neighbors / elapsed
+    gather_gbps = gather_bytes_per_step * args.steps / elapsed / 1e9
+
+    per_kernel = {n: {"launches": c, "avg_ms": ms / c} for n, (c, ms) in kernels.items()}
+    dominant = max(kernels, key=lambda n: kernels[n][1])
+    alg_bytes = {"cache_gather_rows": node_bytes, "gather_rows": edge_bytes}.get(dominant)
+    roofline = None
+    if alg_bytes is not None:
+        achieved = alg_bytes / (per_kernel[dominant]["avg_ms"] * 1e-3) / 1e9
+        roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                    "avg_launch_ms": round(per_kernel[dominant]["avg_ms"], 4), "algorithmic_bytes": alg_bytes,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dominant))}
+
+    # ------------------------------------------------------------------ CPU oracle on a bounded sample
+    cpu = None
+    if args.cpu_roots > 0:
+        import oracle
+        threads = min(16, oracle.max_threads(), len(os.sched_getaffinity(0)))
+        t0 = time.time()
+        g_ref = oracle.tcsr_build(w.src, w.dst, w.ts, w.eid, w.num_nodes, threads)
+        t_build = time.time() - t0
+        roots, times = w.batches[0]
+        nr = min(args.cpu_roots, roots.shape[0])
+        t0 = time.perf_counter()
+        ref = oracle.sample_temporal(g_ref, roots[:nr], times[:nr], k, hops, policy, 42, w.m, w.edge_weight, threads)
+        t_sample = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        if w.node_feat is not None:
+            oracle.gather(w.node_feat, np.concatenate([roots[:nr]] + [o["nbr"].ravel() for o in ref]), threads=threads)
+        if w.edge_feat is not None:
+            oracle.gather(w.edge_feat, np.concatenate([o["eid"].ravel() for o in ref]), threads=threads)
+        t_gather = time.perf_counter() - t0
+        cpu_neighbors = sum(int(o["count"].sum()) for o in ref)
+        # the oracle must agree with what the device produced for the same roots
+        got = batches[0]["out"]
+        step(batches[0])
+        torch.cuda.synchronize()
+        for h in range(hops):
+            assert np.array_equal(got[h]["eid"][:nr * k ** (h + 1)].cpu().numpy(), ref[h]["eid"].ravel()), "GPU/oracle mismatch"
+        sample = (f"first {nr} roots of batch 0, {hops} hops: sampler {t_sample:.2f}s + "
+                  f"{'node' if w.edge_feat is None else 'edge'}-feature gather {t_gather:.2f}s; "
+                  f"oracle T-CSR build ({t_build:.1f}s) not included")
+        if w.edge_feat is None:
+            sample += "; edge-feature gather excluded (the table exists only in device memory)"
+        cpu = {"value": round(cpu_neighbors / (t_sample + t_gather), 1), "unit": "neighbors/s", "cores": threads,
+               "kind": "oracle", "sample": sample}
+
+    hm = hit_miss.tolist()
+    result = {
+        "metric": "sampled temporal neighbors/sec + gather GB/s (% of HBM peak), 2-hop 10x10",
+        "value": round(value, 1), "unit": "neighbors/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int64+bytes", "data": "synthetic",
+        "config": {"workload": w.name + ("" if args.edges is None else f" (reduced to {w.num_edges} events)"),
+                   "events": w.num_edges, "nodes": w.num_nodes, "roots_per_batch": R, "fanout": [k] * hops,
+                   "policy": ["recent", "uniform", "weighted"][policy], "edge_row_bytes": edge_rb,
+                   "node_row_bytes": node_rb, "distinct_batches": len(batches),
+                   "cache_rows": 0 if cache is None else cache.capacity},
+        "gather_GBps": round(gather_gbps, 1), "gather_frac_of_hbm_peak": round(gather_gbps / HBM_PEAK_GBPS, 4),
+        "gather_bytes_per_step": gather_bytes_per_step, "neighbors_per_step": neighbors / args.steps,
+        "cache_hit_rate": None if cache is None or sum(hm) == 0 else round(hm[0] / sum(hm), 4),
+        "tcsr_build": {"entries": int(w.src.shape[0]), "wall_ms": round(build_wall_ms, 2),
+                       "kernel_ms": round(build_dev_ms, 3),
+                       "kernels": {n: round(ms, 3) for n, (_, ms) in build_kernels.items()}},
+        "kernels": {n: {"launches": v["launches"], "avg_ms": round(v["avg_ms"], 4)} for n, v in per_kernel.items()},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -198,6 +198,25 @@ int taser_cache_residents(const taser_cache* c, int32_t* resident_ids_host);
 
 void taser_cache_free(taser_cache* c);
 
+/* ---------------------------------------------------------------------------
+ * Optional per-kernel timing, for benchmarks. Between taser_profile_begin and
+ * taser_profile_end every kernel the library launches (from the thread that
+ * began the session; one session at a time) is bracketed by two HIP events on
+ * the stream it runs on. taser_profile_end waits for those events and fills
+ * `out` (host, caller-allocated, max_entries structs) with one entry per
+ * distinct kernel: its name (static storage), number of launches and summed
+ * device time in milliseconds; *num_entries receives the number of entries.
+ * At most 65536 launches are recorded per session; later ones are not timed.
+ * ------------------------------------------------------------------------- */
+typedef struct taser_kernel_time {
+    const char* name;
+    int64_t launches;
+    double total_ms;
+} taser_kernel_time;
+
+int taser_profile_begin(void);
+int taser_profile_end(taser_kernel_time* out, int32_t max_entries, int32_t* num_entries);
+
 /* Message for the most recent error on the calling thread (static storage). */
 const char* taser_last_error(void);
 

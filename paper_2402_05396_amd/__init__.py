@@ -20,13 +20,17 @@ MAX_K, MAX_M, MAX_HOPS = 64, 64, 3
 
 EXPORTS = ("taser_tcsr_build", "taser_tcsr_size", "taser_tcsr_view", "taser_tcsr_free", "taser_sample_temporal",
            "taser_gather_features", "taser_cache_init", "taser_cache_lookup", "taser_cache_residents",
-           "taser_cache_free", "taser_last_error")
+           "taser_cache_free", "taser_profile_begin", "taser_profile_end", "taser_last_error")
 
 
 class TaserError(RuntimeError):
     def __init__(self, code, message):
         super().__init__(f"taser error {code}: {message}")
         self.code = code
+
+
+class _KernelTime(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char_p), ("launches", ctypes.c_int64), ("total_ms", ctypes.c_double)]
 
 
 class _HopOut(ctypes.Structure):
@@ -59,6 +63,8 @@ def lib():
         L.taser_cache_residents.argtypes = [vp, vp]
         L.taser_cache_free.argtypes = [vp]
         L.taser_cache_free.restype = None
+        L.taser_profile_begin.argtypes = []
+        L.taser_profile_end.argtypes = [ctypes.POINTER(_KernelTime), i32, ctypes.POINTER(i32)]
         L.taser_last_error.restype = ctypes.c_char_p
         _lib = L
     return _lib
@@ -253,3 +259,16 @@ def cache_residents(c):
 
 def cache_free(c):
     c.free()
+
+
+def profile_begin():
+    """taser_profile_begin: start timing every kernel the library launches."""
+    _check(lib().taser_profile_begin())
+
+
+def profile_end(max_entries=64):
+    """taser_profile_end -> {kernel name: (launches, total device ms)}."""
+    arr = (_KernelTime * max_entries)()
+    n = ctypes.c_int32()
+    _check(lib().taser_profile_end(arr, max_entries, ctypes.byref(n)))
+    return {arr[i].name.decode(): (int(arr[i].launches), float(arr[i].total_ms)) for i in range(n.value)}

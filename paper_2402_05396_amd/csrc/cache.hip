@@ -71,13 +71,16 @@ __global__ __launch_bounds__(kThreads) void fill_kernel(int32_t* a, uint32_t n, 
     if (i < n) a[i] = v;
 }
 
+// Grid-stride over the requests; hit/miss counts are summed per block and added
+// to the caller's counters with one atomic pair per block (a pair per wave
+// would put tens of thousands of atomics on one address).
 __global__ __launch_bounds__(kThreads) void classify_kernel(
     const int32_t* __restrict__ ids, int64_t n, int64_t rows, const int32_t* __restrict__ hash_key,
     const int32_t* __restrict__ hash_slot, uint32_t hash_mask, int32_t* miss_key, uint32_t miss_size,
     int32_t* __restrict__ loc, unsigned long long* hit_miss) {
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    bool hit = false, miss = false;
-    if (i < n) {
+    __shared__ uint32_t block_hits[kThreads / kWave], block_misses[kThreads / kWave];
+    uint32_t hits = 0, misses = 0;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kThreads) {
         const int32_t id = ids[i];
         int32_t where = kLocZero;
         if (id >= 0 && id < rows) {
@@ -90,10 +93,10 @@ __global__ __launch_bounds__(kThreads) void classify_kernel(
                 h = (h + 1) & hash_mask;
             }
             if (slot >= 0) {
-                hit = true;
+                ++hits;
                 where = slot;
             } else {
-                miss = true;
+                ++misses;
                 where = kLocHost;
                 if (miss_size) {
                     uint32_t s = hash_id(id, miss_size - 1);
@@ -108,12 +111,25 @@ __global__ __launch_bounds__(kThreads) void classify_kernel(
         }
         loc[i] = where;
     }
-    if (hit_miss) {
-        const unsigned long long hits = __ballot(hit), misses = __ballot(miss);
-        if ((threadIdx.x & (kWave - 1)) == 0) {
-            if (hits) atomicAdd(&hit_miss[0], (unsigned long long)__popcll(hits));
-            if (misses) atomicAdd(&hit_miss[1], (unsigned long long)__popcll(misses));
+    if (!hit_miss) return;
+    for (int d = kWave / 2; d > 0; d >>= 1) {
+        hits += __shfl_down(hits, d, kWave);
+        misses += __shfl_down(misses, d, kWave);
+    }
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    if (lane == 0) {
+        block_hits[wave] = hits;
+        block_misses[wave] = misses;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t h = 0, m = 0;
+        for (int w = 0; w < kThreads / kWave; ++w) {
+            h += block_hits[w];
+            m += block_misses[w];
         }
+        if (h) atomicAdd(&hit_miss[0], (unsigned long long)h);
+        if (m) atomicAdd(&hit_miss[1], (unsigned long long)m);
     }
 }
 
@@ -139,12 +155,14 @@ struct CacheSource {
     int32_t dev_pitch;
     const uint8_t* host_rows;
     int64_t pitch_bytes;
-    __device__ __forceinline__ const uint8_t* row(int64_t i) const {
-        const int32_t where = loc[i];
-        if (where >= 0) return cache_rows + (int64_t)where * dev_pitch;
-        if (where == kLocZero) return nullptr;
-        if (where == kLocHost) return host_rows + (int64_t)ids[i] * pitch_bytes;
-        return stage_rows + (int64_t)(-2 - where) * dev_pitch;
+    __device__ __forceinline__ int32_t key(int64_t i) const { return loc[i]; }
+    __device__ __forceinline__ const uint8_t* address(int32_t where, int64_t i) const {
+        // cache row or staged row: one multiply-add either way, no branch
+        const bool cached = where >= 0;
+        const uint8_t* at = (cached ? cache_rows : stage_rows) + (int64_t)(cached ? where : -2 - where) * dev_pitch;
+        if (where == kLocZero) at = nullptr;
+        if (__builtin_expect(where == kLocHost, 0)) at = host_rows + (int64_t)ids[i] * pitch_bytes;
+        return at;
     }
 };
 
@@ -310,20 +328,28 @@ extern "C" int taser_cache_lookup(taser_cache* c, const int32_t* ids, int64_t n,
         TASER_HIP_TRY(hipMalloc((void**)&c->loc, (size_t)n * sizeof(int32_t)));
         c->loc_capacity = n;
     }
-    const int64_t blocks = (n + kThreads - 1) / kThreads;
-    if (blocks > 0x7fffffffLL) return taser_fail(TASER_E_RANGE, "cache_lookup: n too large");
-    if (c->miss_size)
+    int64_t blocks = (n + kThreads - 1) / kThreads;
+    if (blocks > 2048) blocks = 2048;   // grid-stride: 8 blocks per compute unit
+    if (c->miss_size) {
+        TaserProfileSpan span(stream, "cache_clear_miss_table");
         hipLaunchKernelGGL(fill_kernel, dim3((c->miss_size + kThreads - 1) / kThreads), dim3(kThreads), 0, stream,
                            c->miss_key, c->miss_size, kEmpty);
-    hipLaunchKernelGGL(classify_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, ids, n, c->rows, c->hash_key,
+    }
+    {
+        TaserProfileSpan span(stream, "cache_classify");
+        hipLaunchKernelGGL(classify_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, ids, n, c->rows, c->hash_key,
                        c->hash_slot, c->hash_mask, c->miss_key, c->miss_size, c->loc,
                        reinterpret_cast<unsigned long long*>(hit_miss));
-    if (c->miss_size)
+    }
+    if (c->miss_size) {
+        TaserProfileSpan span(stream, "cache_stage_misses");
         hipLaunchKernelGGL(stage_kernel, dim3((c->miss_size + 3) / 4), dim3(kThreads), 0, stream, c->miss_key,
                            c->miss_size, c->host_rows, c->pitch_bytes, c->row_bytes / 4, c->stage_rows, c->dev_pitch);
+    }
     const CacheSource source{c->loc, ids, c->cache_rows, c->stage_rows, c->dev_pitch, c->host_rows, c->pitch_bytes};
     const int align = taser_gather::common_alignment((uint64_t)c->row_bytes | (uint64_t)c->pitch_bytes |
-                                                     (uint64_t)(uintptr_t)c->host_rows | (uint64_t)(uintptr_t)out);
+                                                     (uint64_t)(uintptr_t)c->host_rows);
+    TaserProfileSpan span(stream, "cache_gather_rows");
     if (!taser_gather::launch(source, align, c->row_bytes, n, out, stream))
         return taser_fail(TASER_E_RANGE, "cache_lookup: %lld rows of %d bytes exceed one launch", (long long)n, c->row_bytes);
     TASER_HIP_TRY(hipGetLastError());

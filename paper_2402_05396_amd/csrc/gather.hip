@@ -11,19 +11,40 @@ struct TableSource {
     int64_t pitch_bytes;
     const int32_t* ids;
     int64_t rows;
-    __device__ __forceinline__ const uint8_t* row(int64_t i) const {
-        const int32_t id = ids[i];
-        return (id < 0 || id >= rows) ? nullptr : table + (int64_t)id * pitch_bytes;
+    __device__ __forceinline__ int32_t key(int64_t i) const { return ids[i]; }
+    __device__ __forceinline__ const uint8_t* address(int32_t id, int64_t) const {
+        const bool ok = id >= 0 && id < rows;
+        const uint8_t* at = table + (int64_t)(ok ? id : 0) * pitch_bytes;   // computed either way: no branch
+        return ok ? at : nullptr;
     }
 };
 
 }  // namespace
 
+// 16 zero bytes in device memory. External linkage and "used": a device variable
+// that no kernel names is otherwise dropped from the code object, and looking it
+// up by symbol then fails inside the runtime.
+__device__ __attribute__((used)) uint32_t taser_zero_chunk_storage[4] = {0u, 0u, 0u, 0u};
+
+const uint8_t* taser_gather::zero_chunk() {
+    // per device: every GPU holds its own copy of the symbol
+    static const uint8_t* cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    if (!cached[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(taser_zero_chunk_storage)) != hipSuccess) return nullptr;
+        cached[dev] = static_cast<const uint8_t*>(p);
+    }
+    return cached[dev];
+}
+
 int taser_launch_gather(const void* table, int64_t rows, int32_t row_bytes, int64_t pitch_bytes, const int32_t* ids,
                         int64_t n, void* out, hipStream_t stream) {
     const int align = taser_gather::common_alignment((uint64_t)row_bytes | (uint64_t)pitch_bytes |
-                                                     (uint64_t)(uintptr_t)table | (uint64_t)(uintptr_t)out);
+                                                     (uint64_t)(uintptr_t)table);
     const TableSource source{static_cast<const uint8_t*>(table), pitch_bytes, ids, rows};
+    TaserProfileSpan span(stream, "gather_rows");
     if (!taser_gather::launch(source, align, row_bytes, n, out, stream))
         return taser_fail(TASER_E_RANGE, "gather: %lld rows of %d bytes exceed one launch", (long long)n, row_bytes);
     TASER_HIP_TRY(hipGetLastError());

@@ -1,12 +1,19 @@
 // Dense row gather: out row i <- the bytes of a source row chosen per i.
 //
-// The output is treated as one flat stream of V-wide elements (V = 16, 8, 4 or
-// 2 bytes, the widest the row size, pitch and base addresses allow). Thread
-// g of the launch produces output element g, so every wave instruction stores
-// 64 consecutive elements (fully coalesced, whatever the row length) and loads
-// runs of consecutive elements from at most a few source rows. Where a row
-// comes from is a functor, so the same kernel serves a table in device memory
-// and the cache's three-way choice (cache rows / staged rows / host memory).
+// The output is treated as one flat, dense stream, whatever the row length.
+// Two kernels:
+//   * gather_chunks_kernel (rows a multiple of 4 bytes, 16-byte aligned
+//     output): every thread produces 16 consecutive output bytes with one
+//     aligned 16-byte non-temporal store. The 16 bytes normally come from one
+//     source row and are read with a single 16-byte load that only needs 4-byte
+//     alignment; a thread whose bytes straddle a row end falls back to 4-byte
+//     loads. A wave instruction therefore moves 1 KiB, rows of any length
+//     (372 B, 1652 B, ...) fill every lane, and the dense output is written in
+//     whole 128-byte lines.
+//   * gather_elems_kernel: the same flat scheme with one V-wide element (2, 4,
+//     8 or 16 bytes) per thread, for rows or bases that are only 2-byte aligned.
+// Where a row comes from is a functor, so the kernels serve both a table in
+// device memory and the cache's choice of cache row / staged row / host row.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -23,15 +30,102 @@ template <> __device__ __forceinline__ u32x2 zero_of<u32x2>() { return u32x2{0, 
 
 constexpr int kThreads = 256;
 constexpr int kUnroll = 4;
-constexpr int kTile = kThreads * kUnroll;   // output elements per block
+constexpr int kTile = kThreads * kUnroll;   // elements (or 16-byte chunks) per block
 
-// Source::row(i) returns the address of the first byte of the row that output
-// row i copies, or nullptr for a row of zeros.
+// 16 bytes that are only known to be 4-byte aligned.
+struct __attribute__((packed, aligned(4))) Chunk16 {
+    u32x4 v;
+};
+
+typedef const __attribute__((address_space(1))) Chunk16* GlobalChunk16Ptr;
+typedef const __attribute__((address_space(1))) uint32_t* GlobalU32Ptr;
+
+// A Source says where output row i comes from, in two steps so that the kernel
+// can issue the (dependent) loads of several rows back to back:
+//   key(i)          a 32-bit token read from memory (an id, a cache location);
+//   address(key, i) first byte of the source row, or nullptr for a zero row.
+// row(i) is the two combined.
+
+// USE_MAGIC: floor(e / d) = umulhi(e, magic) with magic = ceil(2^32 / d), exact
+// for e * d < 2^32 (the launcher checks that); otherwise a plain division.
+template <typename Source, bool USE_MAGIC>
+__global__ __launch_bounds__(kThreads) void gather_chunks_kernel(Source source, uint32_t row_dwords, uint32_t magic,
+                                                                 int64_t total_dwords, int64_t last_row,
+                                                                 const uint8_t* __restrict__ zeros,
+                                                                 uint32_t* __restrict__ out) {
+    const int64_t tile = (int64_t)blockIdx.x * (kTile * 4);   // first output dword of this block
+    int64_t row0;                                               // output row holding it
+    if (tile < ((int64_t)1 << 32)) row0 = (uint32_t)tile / row_dwords;
+    else row0 = tile / (int64_t)row_dwords;
+    const uint32_t col0 = (uint32_t)(tile - row0 * row_dwords);
+
+    // Pass 1 (ALU only): output row and column of each of this thread's chunks.
+    uint32_t col[kUnroll];
+    int64_t row[kUnroll];
+    bool whole[kUnroll], cross[kUnroll];   // inside one row / crossing a row end (neither: past the end)
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const uint32_t local = (threadIdx.x + u * kThreads) * 4u;
+        const uint32_t e = col0 + local;                        // dword offset from the start of row0
+        const uint32_t dr = USE_MAGIC ? __umulhi(e, magic) : e / row_dwords;
+        col[u] = e - dr * row_dwords;
+        row[u] = row0 + dr;
+        const bool live = tile + local < total_dwords;
+        whole[u] = live && col[u] + 4u <= row_dwords;
+        cross[u] = live && !whole[u];
+        if (row[u] > last_row) row[u] = last_row;               // keeps the token load below in bounds
+    }
+    // Pass 2: straight-line code, no branches, so that the four token loads and
+    // then the four 16-byte row loads are in flight together. A chunk with
+    // nothing to load here (zero row, row-crossing, past the end) reads 16 zero
+    // bytes instead of branching around the load.
+    int32_t key[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) key[u] = source.key(row[u]);
+    u32x4 vals[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const uint8_t* base = source.address(key[u], row[u]);
+        const uint8_t* at = (whole[u] && base) ? base + (size_t)col[u] * 4u : zeros;
+        vals[u] = ((GlobalChunk16Ptr)at)->v;
+    }
+    // Pass 3 (rare): chunks that cross one or more row ends, dword by dword.
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        if (!cross[u]) continue;
+        const int64_t d = tile + (threadIdx.x + u * kThreads) * 4u;
+        uint32_t c = col[u];
+        int64_t r = row[u];
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (c >= row_dwords) { c = 0; ++r; }
+            if (d + i < total_dwords) {
+                const uint8_t* base = source.address(source.key(r), r);
+                if (base) w[i] = ((GlobalU32Ptr)base)[c];
+            }
+            ++c;
+        }
+        vals[u] = u32x4{w[0], w[1], w[2], w[3]};
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const int64_t d = tile + (threadIdx.x + u * kThreads) * 4u;
+        if (d + 4 <= total_dwords) {
+            __builtin_nontemporal_store(vals[u], reinterpret_cast<u32x4*>(out + d));
+        } else {
+            const uint32_t w[4] = {vals[u].x, vals[u].y, vals[u].z, vals[u].w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (d + i < total_dwords) out[d + i] = w[i];
+        }
+    }
+}
+
 template <typename V, typename Source>
-__global__ __launch_bounds__(kThreads) void gather_kernel(Source source, uint32_t row_elems,
-                                                          int64_t total_elems, V* __restrict__ out) {
+__global__ __launch_bounds__(kThreads) void gather_elems_kernel(Source source, uint32_t row_elems,
+                                                                int64_t total_elems, V* __restrict__ out) {
     const int64_t tile = (int64_t)blockIdx.x * kTile;
-    // first output row touched by this block and the column of its first element
     int64_t row0;
     if (tile < ((int64_t)1 << 32)) row0 = (uint32_t)tile / row_elems;
     else row0 = tile / (int64_t)row_elems;
@@ -40,13 +134,14 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(Source source, uint32_
     V vals[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-        const uint32_t e = col0 + threadIdx.x + u * kThreads;   // offset from the start of row0
+        const uint32_t e = col0 + threadIdx.x + u * kThreads;
         const uint32_t dr = e / row_elems;
         const uint32_t col = e - dr * row_elems;
         const int64_t g = tile + threadIdx.x + u * kThreads;
         vals[u] = zero_of<V>();
         if (g < total_elems) {
-            const uint8_t* base = source.row(row0 + dr);
+            const int64_t row = row0 + dr;
+            const uint8_t* base = source.address(source.key(row), row);
             if (base) vals[u] = reinterpret_cast<const V*>(base)[col];
         }
     }
@@ -67,26 +162,51 @@ inline int common_alignment(uint64_t bits) {
 }
 
 template <typename V, typename Source>
-inline void launch_typed(const Source& source, int32_t row_bytes, int64_t n, void* out, hipStream_t stream) {
+inline void launch_elems(const Source& source, int32_t row_bytes, int64_t n, void* out, hipStream_t stream) {
     const uint32_t row_elems = (uint32_t)(row_bytes / (int)sizeof(V));
     const int64_t total = n * (int64_t)row_elems;
     const int64_t blocks = (total + kTile - 1) / kTile;
-    hipLaunchKernelGGL((gather_kernel<V, Source>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, source,
+    hipLaunchKernelGGL((gather_elems_kernel<V, Source>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, source,
                        row_elems, total, reinterpret_cast<V*>(out));
 }
 
-// Dispatch on the vector width `align` (from common_alignment). Returns false if
-// the launch would need more blocks than a grid dimension holds.
+// Device address of 16 zero bytes (defined once, in gather.hip); nullptr on failure.
+const uint8_t* zero_chunk();
+
+// `src_align`: power of two dividing the row size, every source pitch and every
+// source base address. Returns false if the launch would need more blocks than
+// a grid dimension holds.
 template <typename Source>
-inline bool launch(const Source& source, int align, int32_t row_bytes, int64_t n, void* out, hipStream_t stream) {
+inline bool launch(const Source& source, int src_align, int32_t row_bytes, int64_t n, void* out, hipStream_t stream) {
     if (n == 0) return true;
+    const uint8_t* zeros = zero_chunk();
+    if (!zeros) return false;
+    const uint64_t out_bits = (uint64_t)(uintptr_t)out;
+    if (src_align >= 4 && (out_bits & 15) == 0) {
+        const uint32_t row_dwords = (uint32_t)row_bytes / 4u;
+        const int64_t total = n * (int64_t)row_dwords;
+        const int64_t blocks = (total + kTile * 4 - 1) / (kTile * 4);
+        if (blocks > 0x7fffffffLL) return false;
+        // the in-block offsets stay below row_dwords + 4 * kTile: exact while that is < 2^32 / row_dwords
+        const bool small = (uint64_t)row_dwords * ((uint64_t)row_dwords + 4u * kTile) < ((uint64_t)1 << 32);
+        if (small && row_dwords > 1) {
+            const uint32_t magic = (uint32_t)((((uint64_t)1 << 32) + row_dwords - 1) / row_dwords);
+            hipLaunchKernelGGL((gather_chunks_kernel<Source, true>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
+                               source, row_dwords, magic, total, n - 1, zeros, reinterpret_cast<uint32_t*>(out));
+        } else {
+            hipLaunchKernelGGL((gather_chunks_kernel<Source, false>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
+                               source, row_dwords, 0u, total, n - 1, zeros, reinterpret_cast<uint32_t*>(out));
+        }
+        return true;
+    }
+    const int align = common_alignment((uint64_t)src_align | out_bits);
     const int64_t total = n * (int64_t)(row_bytes / align);
     if ((total + kTile - 1) / kTile > 0x7fffffffLL) return false;
     switch (align) {
-        case 16: launch_typed<u32x4>(source, row_bytes, n, out, stream); break;
-        case 8: launch_typed<u32x2>(source, row_bytes, n, out, stream); break;
-        case 4: launch_typed<uint32_t>(source, row_bytes, n, out, stream); break;
-        default: launch_typed<uint16_t>(source, row_bytes, n, out, stream); break;
+        case 16: launch_elems<u32x4>(source, row_bytes, n, out, stream); break;
+        case 8: launch_elems<u32x2>(source, row_bytes, n, out, stream); break;
+        case 4: launch_elems<uint32_t>(source, row_bytes, n, out, stream); break;
+        default: launch_elems<uint16_t>(source, row_bytes, n, out, stream); break;
     }
     return true;
 }

@@ -177,6 +177,8 @@ void launch_hop(const taser_tcsr* g, const int32_t* roots, const int64_t* times,
                 uint64_t seed, uint32_t hop, int m, const uint32_t* edge_weight,
                 const taser_hop_out& o, hipStream_t stream) {
     const unsigned grid = (unsigned)((n + kRootsPerBlock - 1) / kRootsPerBlock);
+    static const char* const names[3] = {"sample_hop_recent", "sample_hop_uniform", "sample_hop_weighted"};
+    TaserProfileSpan span(stream, names[POLICY]);
     hipLaunchKernelGGL(sample_hop_kernel<POLICY>, dim3(grid), dim3(kRootsPerBlock * kWave), 0, stream,
                        g->indptr, g->rec, roots, times, n, g->num_nodes, k, (uint32_t)seed, (uint32_t)(seed >> 32),
                        hop, m, edge_weight, o.nbr, o.eid, o.ts, o.count);

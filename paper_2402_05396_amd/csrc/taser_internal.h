@@ -37,3 +37,18 @@ static constexpr int kWave = 64;
 // and the cache (defined in gather.hip). Pointers are device-visible.
 int taser_launch_gather(const void* table, int64_t rows, int32_t row_bytes, int64_t pitch_bytes,
                         const int32_t* ids, int64_t n, void* out, hipStream_t stream);
+
+// Brackets the kernel launches made during its lifetime with a pair of events
+// on `stream` while a taser_profile_begin/_end session is active; otherwise
+// it does nothing. `name` must have static storage.
+class TaserProfileSpan {
+public:
+    TaserProfileSpan(hipStream_t stream, const char* name);
+    ~TaserProfileSpan();
+    TaserProfileSpan(const TaserProfileSpan&) = delete;
+    TaserProfileSpan& operator=(const TaserProfileSpan&) = delete;
+
+private:
+    hipStream_t stream_;
+    long index_;
+};

@@ -306,8 +306,11 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
         TASER_HIP_TRY(hipMemcpyAsync(d_info.p, info, sizeof(info), hipMemcpyHostToDevice, stream));
         unsigned grid = blocks_for(n, kThreads);
         if (grid > 4096) grid = 4096;
-        hipLaunchKernelGGL(inspect_kernel, dim3(grid), dim3(kThreads), 0, stream, src, ts, n, num_nodes,
-                           d_info.as<unsigned long long>());
+        {
+            TaserProfileSpan span(stream, "tcsr_inspect");
+            hipLaunchKernelGGL(inspect_kernel, dim3(grid), dim3(kThreads), 0, stream, src, ts, n, num_nodes,
+                               d_info.as<unsigned long long>());
+        }
         TASER_HIP_TRY(hipGetLastError());
         TASER_HIP_TRY(hipMemcpyAsync(info, d_info.p, sizeof(info), hipMemcpyDeviceToHost, stream));
         TASER_HIP_TRY(hipStreamSynchronize(stream));
@@ -335,8 +338,11 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
     const int64_t hist_len = (int64_t)kBins * num_blocks;
     const unsigned scan_blocks = blocks_for(hist_len, kScanChunk);
     if (n > 0) {
-        hipLaunchKernelGGL(pack_kernel, dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, stream, src, dst, ts,
-                           eid, n, rec_a.as<TaserRec>(), key_a.as<int32_t>());
+        {
+            TaserProfileSpan span(stream, "tcsr_pack");
+            hipLaunchKernelGGL(pack_kernel, dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, stream, src, dst, ts,
+                               eid, n, rec_a.as<TaserRec>(), key_a.as<int32_t>());
+        }
         if (!passes.empty()) {
             TASER_HIP_TRY(rec_b.alloc(n * sizeof(TaserRec)));
             TASER_HIP_TRY(key_b.alloc(n * sizeof(int32_t)));
@@ -344,23 +350,41 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
             TASER_HIP_TRY(partial.alloc((size_t)scan_blocks * sizeof(uint32_t)));
         }
         for (const DigitSpec& d : passes) {
-            hipLaunchKernelGGL(radix_hist_kernel, dim3(num_blocks), dim3(kThreads), 0, stream,
-                               rec_a.as<TaserRec>(), key_a.as<int32_t>(), n, d, hist.as<uint32_t>(), num_blocks);
-            hipLaunchKernelGGL(scan_reduce_kernel, dim3(scan_blocks), dim3(kThreads), 0, stream,
-                               hist.as<uint32_t>(), hist_len, partial.as<uint32_t>());
-            hipLaunchKernelGGL(scan_partials_kernel, dim3(1), dim3(kThreads), 0, stream, partial.as<uint32_t>(),
-                               (int64_t)scan_blocks);
-            hipLaunchKernelGGL(scan_apply_kernel, dim3(scan_blocks), dim3(kThreads), 0, stream,
-                               hist.as<uint32_t>(), hist_len, partial.as<uint32_t>());
-            hipLaunchKernelGGL(radix_scatter_kernel, dim3(num_blocks), dim3(kThreads), 0, stream,
-                               rec_a.as<TaserRec>(), key_a.as<int32_t>(), n, d, hist.as<uint32_t>(), num_blocks,
-                               rec_b.as<TaserRec>(), key_b.as<int32_t>());
+            {
+                TaserProfileSpan span(stream, "tcsr_radix_hist");
+                hipLaunchKernelGGL(radix_hist_kernel, dim3(num_blocks), dim3(kThreads), 0, stream,
+                                   rec_a.as<TaserRec>(), key_a.as<int32_t>(), n, d, hist.as<uint32_t>(), num_blocks);
+            }
+            {
+                TaserProfileSpan span(stream, "tcsr_scan_reduce");
+                hipLaunchKernelGGL(scan_reduce_kernel, dim3(scan_blocks), dim3(kThreads), 0, stream,
+                                   hist.as<uint32_t>(), hist_len, partial.as<uint32_t>());
+            }
+            {
+                TaserProfileSpan span(stream, "tcsr_scan_partials");
+                hipLaunchKernelGGL(scan_partials_kernel, dim3(1), dim3(kThreads), 0, stream, partial.as<uint32_t>(),
+                                   (int64_t)scan_blocks);
+            }
+            {
+                TaserProfileSpan span(stream, "tcsr_scan_apply");
+                hipLaunchKernelGGL(scan_apply_kernel, dim3(scan_blocks), dim3(kThreads), 0, stream,
+                                   hist.as<uint32_t>(), hist_len, partial.as<uint32_t>());
+            }
+            {
+                TaserProfileSpan span(stream, "tcsr_radix_scatter");
+                hipLaunchKernelGGL(radix_scatter_kernel, dim3(num_blocks), dim3(kThreads), 0, stream,
+                                   rec_a.as<TaserRec>(), key_a.as<int32_t>(), n, d, hist.as<uint32_t>(), num_blocks,
+                                   rec_b.as<TaserRec>(), key_b.as<int32_t>());
+            }
             void* t = rec_a.p; rec_a.p = rec_b.p; rec_b.p = t;
             t = key_a.p; key_a.p = key_b.p; key_b.p = t;
         }
     }
-    hipLaunchKernelGGL(indptr_kernel, dim3(blocks_for(n + 1, kThreads)), dim3(kThreads), 0, stream,
-                       key_a.as<int32_t>(), n, num_nodes, indptr.as<int64_t>());
+    {
+        TaserProfileSpan span(stream, "tcsr_indptr");
+        hipLaunchKernelGGL(indptr_kernel, dim3(blocks_for(n + 1, kThreads)), dim3(kThreads), 0, stream,
+                           key_a.as<int32_t>(), n, num_nodes, indptr.as<int64_t>());
+    }
     TASER_HIP_TRY(hipGetLastError());
     TASER_HIP_TRY(hipStreamSynchronize(stream));
 
