@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5, choices=[3, 4, 5])
     ap.add_argument("--edges", type=int, default=None, help="override the event count (smaller = not the named workload)")
+    ap.add_argument("--schedule", default="pipeline", choices=["serial", "overlap", "pipeline"])
+    ap.add_argument("--stage-blocks", type=int, default=16, help="width of the PCIe staging copy when it runs beside other kernels")
     ap.add_argument("--cpu-roots", type=int, default=6000, help="roots of batch 0 the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -111,19 +113,63 @@ def main():
             at_e += n_slots[h]
             r *= k
         batches.append(dict(roots=ids[:R], times=torch.from_numpy(times).to(dev), ids=ids, eids=eids, out=out))
-    edge_out = torch.empty((sum(n_slots), w.edge_dim), dtype=edge_dtype, device=dev)
-    node_out = None if cache is None else torch.empty((n_ids, w.node_feat.shape[1]), dtype=torch.float32, device=dev)
+    # Two sets of output buffers (and two cache handles, i.e. two sets of lookup scratch over
+    # the same resident rows) so that consecutive batches can be in flight together.
+    n_buf = 2
+    edge_out = [torch.empty((sum(n_slots), w.edge_dim), dtype=edge_dtype, device=dev) for _ in range(n_buf)]
+    node_out = [None if cache is None else torch.empty((n_ids, w.node_feat.shape[1]), dtype=torch.float32, device=dev)
+                for _ in range(n_buf)]
+    caches = [cache]
+    if cache is not None:
+        caches.append(T.cache_init(node_host, cap, hot, staging_rows=w.num_nodes - cap))
+        if args.schedule != "serial":
+            for c in caches:
+                T.cache_tune(c, stage_blocks=args.stage_blocks, refresh_before_gather=True)
     hit_miss = torch.zeros(2, dtype=torch.int64, device=dev)
-    stream = torch.cuda.current_stream()
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream()                       # same (default) priority as the main stream
+    ev_sampled = [torch.cuda.Event() for _ in range(n_buf)]
+    ev_staged = [torch.cuda.Event() for _ in range(n_buf)]
 
-    def step(b):
-        T.sample_temporal(g, b["roots"], b["times"], k, hops, policy, 42, w.m, weight, out=b["out"], stream=stream)
-        T.gather_features(edge_table, b["eids"], out=edge_out, stream=stream)
-        if cache is not None:
-            T.cache_lookup(cache, b["ids"], out=node_out, hit_miss=hit_miss, stream=stream)
+    def sample(b):
+        T.sample_temporal(g, b["roots"], b["times"], k, hops, policy, 42, w.m, weight, out=b["out"], stream=main)
 
-    for i in range(args.warmup):
-        step(batches[i % len(batches)])
+    def run(first, count):
+        """`count` passes of the whole path over consecutive batches.
+        serial:   everything on one stream.
+        overlap:  per batch, the PCIe staging of missed node rows runs on a side stream beside
+                  the edge gather.
+        pipeline: the staging of batch i also runs beside the sampling and edge gather of batch
+                  i+1; the node gather of batch i is issued one batch late (two buffer sets)."""
+        pending = None
+        for i in range(count):
+            b, s = batches[(first + i) % len(batches)], i % n_buf
+            sample(b)
+            if cache is None or args.schedule == "serial":
+                T.gather_features(edge_table, b["eids"], out=edge_out[s], stream=main)
+                if cache is not None:
+                    T.cache_lookup(caches[s], b["ids"], out=node_out[s], hit_miss=hit_miss, stream=main)
+                continue
+            ev_sampled[s].record(main)
+            side.wait_event(ev_sampled[s])
+            T.cache_prefetch(caches[s], b["ids"], hit_miss=hit_miss, stream=side)
+            ev_staged[s].record(side)
+            T.gather_features(edge_table, b["eids"], out=edge_out[s], stream=main)
+            if args.schedule == "pipeline":
+                if pending is not None:
+                    pb, ps = pending
+                    main.wait_event(ev_staged[ps])
+                    T.cache_gather(caches[ps], pb["ids"], out=node_out[ps], stream=main)
+                pending = (b, s)
+            else:
+                main.wait_event(ev_staged[s])
+                T.cache_gather(caches[s], b["ids"], out=node_out[s], stream=main)
+        if pending is not None:
+            pb, ps = pending
+            main.wait_event(ev_staged[ps])
+            T.cache_gather(caches[ps], pb["ids"], out=node_out[ps], stream=main)
+
+    run(0, args.warmup)
     torch.cuda.synchronize()
     hit_miss.zero_()
     torch.cuda.synchronize()
@@ -131,8 +177,7 @@ def main():
     # ------------------------------------------------------------------ timed region
     T.profile_begin()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(batches[i % len(batches)])
+    run(0, args.steps)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     kernels = T.profile_end()
@@ -160,6 +205,16 @@ def main():
                     "avg_launch_ms": round(per_kernel[dominant]["avg_ms"], 4), "algorithmic_bytes": alg_bytes,
                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dominant))}
 
+    # A plain streaming kernel of known size (out[i] = in[i] + 1 over int32: 1 GiB read +
+    # 1 GiB written): under rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings calibrate
+    # the counters' unit for the kernels above.
+    calib_src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
+    calib_dst = torch.empty_like(calib_src)
+    torch.cuda.synchronize()
+    torch.add(calib_src, 1, out=calib_dst)
+    torch.cuda.synchronize()
+    del calib_src, calib_dst
+
     # ------------------------------------------------------------------ CPU oracle on a bounded sample
     cpu = None
     if args.cpu_roots > 0:
@@ -182,7 +237,7 @@ def main():
         cpu_neighbors = sum(int(o["count"].sum()) for o in ref)
         # the oracle must agree with what the device produced for the same roots
         got = batches[0]["out"]
-        step(batches[0])
+        run(0, 1)
         torch.cuda.synchronize()
         for h in range(hops):
             assert np.array_equal(got[h]["eid"][:nr * k ** (h + 1)].cpu().numpy(), ref[h]["eid"].ravel()), "GPU/oracle mismatch"
@@ -204,7 +259,7 @@ def main():
                    "events": w.num_edges, "nodes": w.num_nodes, "roots_per_batch": R, "fanout": [k] * hops,
                    "policy": ["recent", "uniform", "weighted"][policy], "edge_row_bytes": edge_rb,
                    "node_row_bytes": node_rb, "distinct_batches": len(batches),
-                   "cache_rows": 0 if cache is None else cache.capacity},
+                   "cache_rows": 0 if cache is None else cache.capacity, "schedule": args.schedule},
         "gather_GBps": round(gather_gbps, 1), "gather_frac_of_hbm_peak": round(gather_gbps / HBM_PEAK_GBPS, 4),
         "gather_bytes_per_step": gather_bytes_per_step, "neighbors_per_step": neighbors / args.steps,
         "cache_hit_rate": None if cache is None or sum(hm) == 0 else round(hm[0] / sum(hm), 4),

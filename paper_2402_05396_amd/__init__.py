@@ -19,7 +19,7 @@ INPUT_ON_DEVICE = 1
 MAX_K, MAX_M, MAX_HOPS = 64, 64, 3
 
 EXPORTS = ("taser_tcsr_build", "taser_tcsr_size", "taser_tcsr_view", "taser_tcsr_free", "taser_sample_temporal",
-           "taser_gather_features", "taser_cache_init", "taser_cache_lookup", "taser_cache_residents",
+           "taser_gather_features", "taser_cache_init", "taser_cache_lookup", "taser_cache_prefetch", "taser_cache_gather", "taser_cache_tune", "taser_cache_residents",
            "taser_cache_free", "taser_profile_begin", "taser_profile_end", "taser_last_error")
 
 
@@ -60,6 +60,9 @@ def lib():
         L.taser_gather_features.argtypes = [vp, i64, i32, i64, vp, i64, vp, vp]
         L.taser_cache_init.argtypes = [vp, i64, i32, i64, i64, vp, u64, i64, vp, ctypes.POINTER(vp)]
         L.taser_cache_lookup.argtypes = [vp, vp, i64, vp, vp, vp]
+        L.taser_cache_prefetch.argtypes = [vp, vp, i64, vp, vp]
+        L.taser_cache_gather.argtypes = [vp, vp, i64, vp, vp]
+        L.taser_cache_tune.argtypes = [vp, i32, i32]
         L.taser_cache_residents.argtypes = [vp, vp]
         L.taser_cache_free.argtypes = [vp]
         L.taser_cache_free.restype = None
@@ -249,6 +252,31 @@ def cache_lookup(c, ids, out=None, hit_miss=None, stream=None):
         _want(hit_miss, torch.int64, "hit_miss")
     _check(lib().taser_cache_lookup(c.handle, _ptr(ids), n, _ptr(out), _ptr(hit_miss), _stream(stream)))
     return out
+
+
+def cache_prefetch(c, ids, hit_miss=None, stream=None):
+    """taser_cache_prefetch: classify the requests and stage the missing rows."""
+    _want(ids, torch.int32, "ids")
+    if hit_miss is not None:
+        _want(hit_miss, torch.int64, "hit_miss")
+    _check(lib().taser_cache_prefetch(c.handle, _ptr(ids), ids.numel(), _ptr(hit_miss), _stream(stream)))
+
+
+def cache_gather(c, ids, out=None, stream=None):
+    """taser_cache_gather: the dense output for the ids of the latest cache_prefetch."""
+    _want(ids, torch.int32, "ids")
+    n = ids.numel()
+    if out is None:
+        out = torch.empty((n, c.row_elems), dtype=c.host_table.dtype, device=ids.device)
+    elif out.dtype != c.host_table.dtype or not out.is_contiguous() or out.numel() < n * c.row_elems:
+        raise TypeError("out: expected a contiguous device tensor of the table's dtype with n*d elements")
+    _check(lib().taser_cache_gather(c.handle, _ptr(ids), n, _ptr(out), _stream(stream)))
+    return out
+
+
+def cache_tune(c, stage_blocks=0, refresh_before_gather=False):
+    """taser_cache_tune."""
+    _check(lib().taser_cache_tune(c.handle, stage_blocks, 1 if refresh_before_gather else 0))
 
 
 def cache_residents(c):

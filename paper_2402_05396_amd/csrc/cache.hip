@@ -10,7 +10,8 @@
 // access a hot non-resident row is otherwise re-read hundreds of times per
 // batch over a bus 100x slower than HBM).
 //
-// A lookup is four launches on the caller's stream:
+// A lookup is four launches (1-3 = taser_cache_prefetch, 4 = taser_cache_gather;
+// split so that a caller can run the bus-bound part beside other work):
 //   1. clear the per-call miss table;
 //   2. classify: every request probes the resident hash; a miss claims a slot
 //      of the miss table (compare-and-swap on the id, the slot index doubles as
@@ -61,6 +62,10 @@ struct taser_cache {
     uint32_t miss_size;         // 0 or a power of two
     int32_t* loc;               // device [loc_capacity], per-request outcome
     int64_t loc_capacity;
+    const int32_t* prefetched_ids;   // what `loc` currently describes (set by taser_cache_prefetch)
+    int64_t prefetched_n;
+    int stage_blocks;                // width of the host -> staging copy, in 256-thread blocks
+    bool refresh_before_gather;      // see rewrite_kernel
     std::vector<int32_t>* residents;   // host copy, slot order
 };
 
@@ -133,18 +138,71 @@ __global__ __launch_bounds__(kThreads) void classify_kernel(
     }
 }
 
-// One wave per miss-table slot: copy the claimed row from host memory.
+// Copies every claimed row host -> staging. The copy is bound by the bus, not by
+// the GPU, so it runs on a few hundred waves only (each keeps a whole row, up to
+// 2 KiB, in flight) and leaves the compute units to whatever runs beside it:
+// a wave reads 64 table slots at a time and walks the claimed ones.
+constexpr int kStageBlocks = 64;
+
 __global__ __launch_bounds__(kThreads) void stage_kernel(const int32_t* __restrict__ miss_key, uint32_t miss_size,
                                                          const uint8_t* __restrict__ host_rows, int64_t pitch_bytes,
-                                                         int32_t row_words, uint8_t* __restrict__ stage_rows,
+                                                         uint32_t row_dwords, uint8_t* __restrict__ stage_rows,
                                                          int32_t dev_pitch) {
-    const uint32_t s = blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
-    if (s >= miss_size) return;
-    const int32_t id = miss_key[s];
-    if (id < 0) return;
-    const uint32_t* from = reinterpret_cast<const uint32_t*>(host_rows + (int64_t)id * pitch_bytes);
-    uint32_t* to = reinterpret_cast<uint32_t*>(stage_rows + (int64_t)s * dev_pitch);
-    for (int32_t w = threadIdx.x & (kWave - 1); w < row_words; w += kWave) to[w] = from[w];
+    using taser_gather::Chunk16;
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
+    const uint32_t num_waves = gridDim.x * (kThreads / kWave);
+    const uint32_t chunks = row_dwords / 4u, tail = row_dwords & 3u;
+    for (uint32_t base = wave * kWave; base < miss_size; base += num_waves * kWave) {   // miss_size % 64 == 0
+        const int32_t key = miss_key[base + lane];
+        uint64_t claimed = __ballot(key >= 0);
+        while (claimed) {
+            const int l = __ffsll((long long)claimed) - 1;
+            claimed &= claimed - 1;
+            const int32_t id = __builtin_amdgcn_readlane(key, l);
+            const uint8_t* from = host_rows + (int64_t)id * pitch_bytes;
+            uint8_t* to = stage_rows + (int64_t)(base + l) * dev_pitch;
+            // 16-byte pieces (4-byte aligned on both sides), two per lane in flight
+            for (uint32_t c = lane; c < chunks; c += 2 * kWave) {
+                const uint32_t c2 = c + kWave;
+                const Chunk16 a = reinterpret_cast<const Chunk16*>(from)[c];
+                Chunk16 b = a;
+                if (c2 < chunks) b = reinterpret_cast<const Chunk16*>(from)[c2];
+                reinterpret_cast<Chunk16*>(to)[c] = a;
+                if (c2 < chunks) reinterpret_cast<Chunk16*>(to)[c2] = b;
+            }
+            if (lane < tail)
+                reinterpret_cast<uint32_t*>(to)[chunks * 4u + lane] = reinterpret_cast<const uint32_t*>(from)[chunks * 4u + lane];
+        }
+    }
+}
+
+// Re-writes up to three arrays of 32-bit words in place with the bytes they
+// already hold (`zero` is 0; it only keeps the stores from being optimised
+// away). Why: measured on MI355X, the memory-side cache keeps lines that were
+// recently written but does not take lines back in on read misses. When other
+// streaming work ran between the staging and the gather, the gather's small
+// read working set (locations, resident rows, staged rows) has been evicted,
+// every L2 miss then goes to HBM, and the gather runs 1.4x slower. Touching
+// the working set (tens of MB) costs a few tens of microseconds.
+struct RewriteJob {
+    uint32_t* words[3];
+    int64_t count[3];
+};
+
+__global__ __launch_bounds__(kThreads) void rewrite_kernel(RewriteJob job, uint32_t zero) {
+    using taser_gather::u32x4;
+    for (int a = 0; a < 3; ++a) {
+        u32x4* quads = reinterpret_cast<u32x4*>(job.words[a]);   // bases are allocation starts: 16-byte aligned
+        const int64_t nq = job.count[a] / 4;
+        for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nq; i += (int64_t)gridDim.x * kThreads) {
+            u32x4 v = quads[i];
+            v.x ^= zero;
+            quads[i] = v;
+        }
+        const int64_t t = nq * 4 + (int64_t)blockIdx.x * kThreads + threadIdx.x;
+        if (t < job.count[a]) job.words[a][t] ^= zero;
+    }
 }
 
 struct CacheSource {
@@ -230,6 +288,8 @@ extern "C" int taser_cache_init(const void* host_table, int64_t rows, int32_t ro
     c->capacity = capacity_rows;
     c->host_rows = static_cast<const uint8_t*>(attr.devicePointer);
     c->dev_pitch = row_bytes;
+    c->stage_blocks = kStageBlocks;
+    c->refresh_before_gather = false;
     c->residents = new (std::nothrow) std::vector<int32_t>();
     if (!c->residents) { destroy(c); return taser_fail(TASER_E_OOM, "cache_init: host allocation failed"); }
 
@@ -276,7 +336,7 @@ extern "C" int taser_cache_init(const void* host_table, int64_t rows, int32_t ro
         h_key[h] = res[(size_t)s];
         h_slot[h] = (int32_t)s;
     }
-    c->miss_size = staging_rows > 0 ? pow2_at_least((uint64_t)staging_rows * 2) : 0;
+    c->miss_size = staging_rows > 0 ? pow2_at_least((uint64_t)(staging_rows > 32 ? staging_rows : 32) * 2) : 0;   // >= 64
 
 #define CACHE_TRY(expr)                                               \
     do {                                                              \
@@ -311,13 +371,14 @@ extern "C" int taser_cache_init(const void* host_table, int64_t rows, int32_t ro
     return TASER_OK;
 }
 
-extern "C" int taser_cache_lookup(taser_cache* c, const int32_t* ids, int64_t n, void* out, uint64_t* hit_miss,
-                                  void* hip_stream) {
-    if (!c) return taser_fail(TASER_E_ARG, "cache_lookup: null cache");
-    if (n < 0) return taser_fail(TASER_E_ARG, "cache_lookup: n = %lld", (long long)n);
+extern "C" int taser_cache_prefetch(taser_cache* c, const int32_t* ids, int64_t n, uint64_t* hit_miss,
+                                    void* hip_stream) {
+    if (!c) return taser_fail(TASER_E_ARG, "cache_prefetch: null cache");
+    if (n < 0) return taser_fail(TASER_E_ARG, "cache_prefetch: n = %lld", (long long)n);
+    c->prefetched_ids = nullptr;
+    c->prefetched_n = 0;
     if (n == 0) return TASER_OK;
-    if (!ids || !out) return taser_fail(TASER_E_ARG, "cache_lookup: null ids or out");
-    if ((uintptr_t)out & 3) return taser_fail(TASER_E_ARG, "cache_lookup: out must be 4-byte aligned");
+    if (!ids) return taser_fail(TASER_E_ARG, "cache_prefetch: null ids");
     hipStream_t stream = (hipStream_t)hip_stream;
     if (n > c->loc_capacity) {
         // grows only; the old buffer may still be in use by earlier work on this stream
@@ -337,22 +398,68 @@ extern "C" int taser_cache_lookup(taser_cache* c, const int32_t* ids, int64_t n,
     }
     {
         TaserProfileSpan span(stream, "cache_classify");
-        hipLaunchKernelGGL(classify_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, ids, n, c->rows, c->hash_key,
-                       c->hash_slot, c->hash_mask, c->miss_key, c->miss_size, c->loc,
-                       reinterpret_cast<unsigned long long*>(hit_miss));
+        hipLaunchKernelGGL(classify_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, ids, n, c->rows,
+                           c->hash_key, c->hash_slot, c->hash_mask, c->miss_key, c->miss_size, c->loc,
+                           reinterpret_cast<unsigned long long*>(hit_miss));
     }
     if (c->miss_size) {
         TaserProfileSpan span(stream, "cache_stage_misses");
-        hipLaunchKernelGGL(stage_kernel, dim3((c->miss_size + 3) / 4), dim3(kThreads), 0, stream, c->miss_key,
-                           c->miss_size, c->host_rows, c->pitch_bytes, c->row_bytes / 4, c->stage_rows, c->dev_pitch);
+        hipLaunchKernelGGL(stage_kernel, dim3(c->stage_blocks), dim3(kThreads), 0, stream, c->miss_key, c->miss_size,
+                           c->host_rows, c->pitch_bytes, (uint32_t)c->row_bytes / 4u, c->stage_rows, c->dev_pitch);
     }
+    TASER_HIP_TRY(hipGetLastError());
+    c->prefetched_ids = ids;
+    c->prefetched_n = n;
+    return TASER_OK;
+}
+
+extern "C" int taser_cache_gather(taser_cache* c, const int32_t* ids, int64_t n, void* out, void* hip_stream) {
+    if (!c) return taser_fail(TASER_E_ARG, "cache_gather: null cache");
+    if (n < 0) return taser_fail(TASER_E_ARG, "cache_gather: n = %lld", (long long)n);
+    if (ids != c->prefetched_ids || n != c->prefetched_n)
+        return taser_fail(TASER_E_ARG, "cache_gather: not preceded by taser_cache_prefetch of the same ids and n");
+    if (n == 0) return TASER_OK;
+    if (!out) return taser_fail(TASER_E_ARG, "cache_gather: null out");
+    if ((uintptr_t)out & 3) return taser_fail(TASER_E_ARG, "cache_gather: out must be 4-byte aligned");
+    hipStream_t stream = (hipStream_t)hip_stream;
     const CacheSource source{c->loc, ids, c->cache_rows, c->stage_rows, c->dev_pitch, c->host_rows, c->pitch_bytes};
     const int align = taser_gather::common_alignment((uint64_t)c->row_bytes | (uint64_t)c->pitch_bytes |
                                                      (uint64_t)(uintptr_t)c->host_rows);
+    if (c->refresh_before_gather) {
+        RewriteJob job;
+        job.words[0] = reinterpret_cast<uint32_t*>(c->loc);
+        job.count[0] = n;
+        job.words[1] = reinterpret_cast<uint32_t*>(c->cache_rows);
+        job.count[1] = c->capacity * (int64_t)c->dev_pitch / 4;
+        job.words[2] = reinterpret_cast<uint32_t*>(c->stage_rows);
+        job.count[2] = (int64_t)c->miss_size * c->dev_pitch / 4;
+        TaserProfileSpan span(stream, "cache_refresh_working_set");
+        hipLaunchKernelGGL(rewrite_kernel, dim3(2048), dim3(kThreads), 0, stream, job, 0u);
+    }
     TaserProfileSpan span(stream, "cache_gather_rows");
     if (!taser_gather::launch(source, align, c->row_bytes, n, out, stream))
-        return taser_fail(TASER_E_RANGE, "cache_lookup: %lld rows of %d bytes exceed one launch", (long long)n, c->row_bytes);
+        return taser_fail(TASER_E_RANGE, "cache_gather: %lld rows of %d bytes exceed one launch", (long long)n, c->row_bytes);
     TASER_HIP_TRY(hipGetLastError());
+    return TASER_OK;
+}
+
+extern "C" int taser_cache_lookup(taser_cache* c, const int32_t* ids, int64_t n, void* out, uint64_t* hit_miss,
+                                  void* hip_stream) {
+    if (!c) return taser_fail(TASER_E_ARG, "cache_lookup: null cache");
+    if (n < 0) return taser_fail(TASER_E_ARG, "cache_lookup: n = %lld", (long long)n);
+    if (n == 0) return TASER_OK;
+    if (!ids || !out) return taser_fail(TASER_E_ARG, "cache_lookup: null ids or out");
+    if ((uintptr_t)out & 3) return taser_fail(TASER_E_ARG, "cache_lookup: out must be 4-byte aligned");
+    const int rc = taser_cache_prefetch(c, ids, n, hit_miss, hip_stream);
+    if (rc != TASER_OK) return rc;
+    return taser_cache_gather(c, ids, n, out, hip_stream);
+}
+
+extern "C" int taser_cache_tune(taser_cache* c, int32_t stage_blocks, int32_t refresh_before_gather) {
+    if (!c) return taser_fail(TASER_E_ARG, "cache_tune: null cache");
+    if (stage_blocks < 0 || stage_blocks > 4096) return taser_fail(TASER_E_RANGE, "cache_tune: stage_blocks = %d outside [0, 4096]", stage_blocks);
+    if (stage_blocks > 0) c->stage_blocks = stage_blocks;
+    c->refresh_before_gather = refresh_before_gather != 0;
     return TASER_OK;
 }
 

@@ -170,8 +170,8 @@ def procedural_table_torch(seed, rows, dim, dtype, pitch_elems, device, chunk_ro
         x ^= lsr(x, 32)
         y = x * _s64(_PE)
         y ^= lsr(y, 31)
-        s = torch.zeros_like(x)
-        for b in range(8):
+        s = x & 255
+        for b in range(1, 8):
             s += (x >> (8 * b)) & 255
         for b in range(4):
             s += (y >> (8 * b + 16)) & 255

@@ -330,3 +330,29 @@ def test_cache_rejects_unpinned_and_bad_residents():
     # an error from the library leaves HIP usable
     c = T.cache_init(pinned, 2, torch.tensor([5, 6], dtype=torch.int32))
     assert T.cache_lookup(c, dev(np.array([5, 1], np.int32))).abs().sum().item() == 0
+
+
+def test_cache_prefetch_then_gather_on_two_streams():
+    """The two halves of a lookup, the bus-bound half on a side stream, joined by events;
+    a gather that does not match the latest prefetch is refused."""
+    rng = np.random.default_rng(5)
+    rows, dim = 3000, 93
+    host = torch.from_numpy(rng.standard_normal((rows, dim)).astype(np.float32)).pin_memory()
+    c = T.cache_init(host, 600, None, seed=1, staging_rows=2400)
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    for n in (50000, 777, 50001):
+        T.cache_tune(c, stage_blocks=3 if n == 777 else 16, refresh_before_gather=(n != 50000))
+        ids_np = np.minimum(rng.zipf(1.2, n) - 1, rows - 1).astype(np.int32)
+        ids = dev(ids_np)
+        done_ids, staged = torch.cuda.Event(), torch.cuda.Event()
+        done_ids.record(main)
+        side.wait_event(done_ids)
+        T.cache_prefetch(c, ids, stream=side)
+        staged.record(side)
+        main.wait_event(staged)
+        out = T.cache_gather(c, ids, stream=main)
+        torch.cuda.synchronize()
+        assert out.cpu().numpy().tobytes() == oracle.gather(host.numpy(), ids_np).tobytes()
+    with pytest.raises(T.TaserError) as e:
+        T.cache_gather(c, ids[:10])
+    assert e.value.code == -1

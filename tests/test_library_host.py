@@ -78,7 +78,12 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert lib.taser_cache_init(one, 4, 16, 16, 5, None, 0, 0, None, ctypes.byref(c)) == E_RANGE
     assert lib.taser_cache_init(one, 4, 16, 16, 1, None, 0, -1, None, ctypes.byref(c)) == E_RANGE
     assert lib.taser_cache_lookup(None, one, 1, one, None, None) == E_ARG
+    assert lib.taser_cache_prefetch(None, one, 1, None, None) == E_ARG
+    assert lib.taser_cache_gather(None, one, 1, one, None) == E_ARG
+    assert lib.taser_cache_tune(None, 1, 0) == E_ARG
     assert lib.taser_cache_residents(None, None) == E_ARG
+    n = ctypes.c_int32()
+    assert lib.taser_profile_end(None, 4, ctypes.byref(n)) == E_ARG
     lib.taser_tcsr_free(None)
     lib.taser_cache_free(None)
 
