@@ -1,4 +1,6 @@
-// Temporal neighbor finding on gfx950: one 64-lane wavefront per root.
+// Temporal neighbor finding on gfx950: one group of 16, 32 or 64 lanes of a
+// wavefront per root (the smallest that holds the k slots, or the m candidates
+// of the weighted policy).
 //
 // What is computed follows TASER (arXiv 2402.05396) Sec. 2.1 (temporal
 // neighborhood, uniform / most-recent finders), Alg. 2 (pivot search, then one
@@ -7,15 +9,16 @@
 //
 // How it is computed differs from Alg. 2's block-per-root / single-thread
 // binary search / shared-memory bitmap with atomic retry:
-//   * the pivot is found by a wave-wide 64-ary search: every round all 64
-//     lanes probe one timestamp each and a ballot narrows the range 65-fold,
-//     so a 2^25-entry list needs 5 dependent memory rounds instead of 25;
+//   * the pivot is found by a cooperative (G+1)-ary search: every round the G
+//     lanes of a root probe one timestamp each and a ballot narrows the range
+//     (G+1)-fold, so a 2^25-entry list needs 5-7 dependent memory rounds
+//     instead of 25;
 //   * selection without replacement is a partial Fisher-Yates shuffle whose
 //     random draws come from a counter-based generator keyed by
 //     (seed, hop, root index, slot). No atomics, no retries: the result is a
 //     pure function of the inputs, independent of scheduling;
 //   * weighted selection keeps the candidate window in registers (one lane per
-//     candidate) and uses integer wave prefix sums.
+//     candidate) and uses integer prefix sums across the group's lanes.
 #include "taser_internal.h"
 
 namespace {
@@ -43,35 +46,50 @@ __device__ __forceinline__ uint64_t draw64(uint32_t seed_lo, uint32_t seed_hi, u
     return ((uint64_t)c[1] << 32) | c[0];
 }
 
-// ---- wave helpers ----------------------------------------------------------
-__device__ __forceinline__ uint32_t bcast32(uint32_t v, int src_lane) {
-    return (uint32_t)__builtin_amdgcn_readlane((int)v, src_lane);
+// ---- group helpers ---------------------------------------------------------
+// A wavefront is split into 64/G groups of G consecutive lanes (G = 16, 32 or
+// 64), one root per group. `sub` is a lane's index inside its group.
+template <int G> __device__ __forceinline__ uint64_t group_bits(uint64_t wave_ballot, int group) {
+    if (G == 64) return wave_ballot;
+    return (wave_ballot >> (group * G)) & (((uint64_t)1 << G) - 1);
 }
-__device__ __forceinline__ uint64_t bcast64(uint64_t v, int src_lane) {
-    return ((uint64_t)bcast32((uint32_t)(v >> 32), src_lane) << 32) | bcast32((uint32_t)v, src_lane);
+template <int G> __device__ __forceinline__ uint32_t group_get(uint32_t v, int sub_lane) {
+    return (uint32_t)__shfl((int)v, sub_lane, G);
 }
-// Number of entries in [lo, hi) with ts < t, for a time-sorted list.
-// All lanes take part; lo, hi, t are wave-uniform.
-__device__ __forceinline__ int64_t wave_cutoff(const TaserRec* __restrict__ rec, int64_t lo,
-                                               int64_t hi, int64_t t, int lane) {
+template <int G> __device__ __forceinline__ uint64_t group_get64(uint64_t v, int sub_lane) {
+    return ((uint64_t)group_get<G>((uint32_t)(v >> 32), sub_lane) << 32) | group_get<G>((uint32_t)v, sub_lane);
+}
+
+// Number of entries in [lo, hi) with ts < t, for a time-sorted list: a (G+1)-ary
+// search. Every round the G lanes of a group probe G pivots that cut the open
+// range into G+1 nearly equal parts and a ballot narrows it. Groups of one wave
+// run different numbers of rounds; a finished group idles. lo, hi, t are uniform
+// inside a group; every lane of the wave must call this.
+template <int G>
+__device__ __forceinline__ int64_t group_cutoff(const TaserRec* __restrict__ rec, int64_t lo, int64_t hi,
+                                                int64_t t, int group, int sub) {
     int64_t a = lo, b = hi;   // entries before a are < t, entries from b on are >= t
-    while (b - a > kWave) {
-        // 64 pivots that cut [a, b) into 65 nearly equal parts: pivot i sits at
-        // a + floor(len * (i + 1) / 65), split as q*(i+1) + floor(r*(i+1)/65) so
-        // that everything stays in 32 bits (len < 2^31).
+    bool wide = b - a > G;
+    while (__ballot(wide)) {
+        // pivot i (1-based) sits at a + floor(len * i / (G+1)), computed as
+        // q*i + floor(r*i/(G+1)) so that everything stays in 32 bits (len < 2^31)
         const uint32_t len = (uint32_t)(b - a);
-        const uint32_t q65 = len / 65u, r65 = len - q65 * 65u;
-        auto pivot = [&](uint32_t i1) { return a + (int64_t)(q65 * i1 + (r65 * i1) / 65u); };
-        const bool before = rec[pivot((uint32_t)lane + 1u)].ts < t;
-        const uint32_t c = (uint32_t)__popcll(__ballot(before));   // the predicate is monotone in the lane
-        const int64_t na = (c > 0) ? pivot(c) + 1 : a;
-        const int64_t nb = (c < (uint32_t)kWave) ? pivot(c + 1u) : b;
-        a = na;
-        b = nb;
+        const uint32_t q = len / (uint32_t)(G + 1), r = len - q * (uint32_t)(G + 1);
+        auto pivot = [&](uint32_t i1) { return a + (int64_t)(q * i1 + (r * i1) / (uint32_t)(G + 1)); };
+        bool before = false;
+        if (wide) before = rec[pivot((uint32_t)sub + 1u)].ts < t;
+        const uint32_t c = (uint32_t)__popcll(group_bits<G>(__ballot(before), group));   // monotone in the lane
+        if (wide) {
+            const int64_t na = (c > 0) ? pivot(c) + 1 : a;
+            const int64_t nb = (c < (uint32_t)G) ? pivot(c + 1u) : b;
+            a = na;
+            b = nb;
+            wide = b - a > G;
+        }
     }
-    const int64_t p = a + lane;
+    const int64_t p = a + sub;
     const bool before = (p < b) && (rec[p].ts < t);
-    return a + __popcll(__ballot(before)) - lo;
+    return a + __popcll(group_bits<G>(__ballot(before), group)) - lo;
 }
 
 __device__ __forceinline__ void store_slot(int32_t* o_nbr, int32_t* o_eid, int64_t* o_ts,
@@ -81,107 +99,132 @@ __device__ __forceinline__ void store_slot(int32_t* o_nbr, int32_t* o_eid, int64
     o_ts[at] = r.ts;
 }
 
-constexpr int kRootsPerBlock = 4;   // 256 threads
+constexpr int kThreads = 256;
 
-template <int POLICY>
-__global__ __launch_bounds__(kRootsPerBlock* kWave) void sample_hop_kernel(
+// G lanes per root: G >= k, and G >= m for the weighted policy.
+template <int POLICY, int G>
+__global__ __launch_bounds__(kThreads) void sample_hop_kernel(
     const int64_t* __restrict__ indptr, const TaserRec* __restrict__ rec,
     const int32_t* __restrict__ roots, const int64_t* __restrict__ times, int64_t num_roots,
     int32_t num_nodes, int k, uint32_t seed_lo, uint32_t seed_hi, uint32_t hop, int m, const uint32_t* __restrict__ edge_weight,
     int32_t* __restrict__ o_nbr, int32_t* __restrict__ o_eid, int64_t* __restrict__ o_ts,
     int32_t* __restrict__ o_count) {
+    constexpr int kGroups = kWave / G;                         // roots per wave
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t q = (int64_t)blockIdx.x * kRootsPerBlock + wave;   // root index, wave-uniform
-    if (q >= num_roots) return;
+    const int group = lane / G, sub = lane % G;
+    const int64_t q = ((int64_t)blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6)) * kGroups + group;   // root index
+    const bool live = q < num_roots;
 
-    const int32_t v = roots[q];
-    int64_t lo = 0, cnt = 0;
-    if (v >= 0 && v < num_nodes) {   // anything else is a root without neighbors
-        const int64_t t = times[q];
-        lo = indptr[v];
-        const int64_t hi = indptr[v + 1];
-        cnt = wave_cutoff(rec, lo, hi, t, lane);
+    int64_t lo = 0, hi = 0, t = 0;
+    if (live) {
+        const int32_t v = roots[q];
+        if (v >= 0 && v < num_nodes) {   // anything else is a root without neighbors
+            t = times[q];
+            lo = indptr[v];
+            hi = indptr[v + 1];
+        }
     }
+    const int64_t cnt = group_cutoff<G>(rec, lo, hi, t, group, sub);   // 0 for dead groups (lo == hi)
     const int64_t out0 = q * k;
     const TaserRec pad = {0, -1, -1};
-    int filled;
+    int filled = 0;
 
-    if (POLICY == TASER_RECENT || (POLICY == TASER_UNIFORM && cnt <= k)) {
+    // All lanes of the wave walk through the same code; what a group does not need is masked.
+    if (POLICY == TASER_RECENT) {
         filled = (int)(cnt < k ? cnt : k);
-        if (lane < k) store_slot(o_nbr, o_eid, o_ts, out0 + lane, lane < filled ? rec[lo + cnt - 1 - lane] : pad);
+        if (live && sub < k) store_slot(o_nbr, o_eid, o_ts, out0 + sub, sub < filled ? rec[lo + cnt - 1 - sub] : pad);
     } else if (POLICY == TASER_UNIFORM) {
-        // Partial Fisher-Yates over the virtual array a[x] = x, x in [0, cnt).
-        // Lane j owns step j: it remembers the position it overwrote (pos) and
-        // the value it put there (val); a lookup of a[x] at step j is the val
-        // of the latest earlier step that wrote x, else x itself.
-        filled = k;
+        // cnt <= k: everything, most recent first. Otherwise a partial Fisher-Yates
+        // over the virtual array a[x] = x, x in [0, cnt): lane j of the group owns
+        // step j; it remembers the position it overwrote (pos) and the value it put
+        // there (val); a lookup of a[x] at step j is the val of the latest earlier
+        // step that wrote x, else x itself.
+        const bool shuffle = cnt > k;
+        filled = (int)(shuffle ? k : cnt);
         uint32_t pos = 0, val = 0, idx = 0;
-        if (lane < k) {
-            const uint64_t u = draw64(seed_lo, seed_hi, hop, (uint64_t)q, (uint32_t)lane);
-            pos = (uint32_t)lane + (uint32_t)__umul64hi(u, (uint64_t)(cnt - lane));
+        if (shuffle && sub < k) {
+            const uint64_t u = draw64(seed_lo, seed_hi, hop, (uint64_t)q, (uint32_t)sub);
+            pos = (uint32_t)sub + (uint32_t)__umul64hi(u, (uint64_t)(cnt - sub));
         }
-        for (int j = 0; j < k; ++j) {
-            const uint32_t r = bcast32(pos, j);
-            const bool earlier = lane < j;
-            const uint64_t hit_r = __ballot(earlier && pos == r);
-            const uint64_t hit_j = __ballot(earlier && pos == (uint32_t)j);
-            const uint32_t a_r = hit_r ? bcast32(val, 63 - __clzll((long long)hit_r)) : r;
-            const uint32_t a_j = hit_j ? bcast32(val, 63 - __clzll((long long)hit_j)) : (uint32_t)j;
-            if (lane == j) {
-                idx = a_r;
-                val = a_j;
+        if (__ballot(shuffle)) {
+            for (int j = 0; j < k; ++j) {
+                const uint32_t r = group_get<G>(pos, j);
+                const bool earlier = sub < j;
+                const uint64_t hit_r = group_bits<G>(__ballot(earlier && pos == r), group);
+                const uint64_t hit_j = group_bits<G>(__ballot(earlier && pos == (uint32_t)j), group);
+                // the shuffles are executed by every lane; lanes without a hit read lane 0 and drop it
+                const uint32_t v_r = group_get<G>(val, hit_r ? 63 - __clzll((long long)hit_r) : 0);
+                const uint32_t v_j = group_get<G>(val, hit_j ? 63 - __clzll((long long)hit_j) : 0);
+                if (sub == j) {
+                    idx = hit_r ? v_r : r;
+                    val = hit_j ? v_j : (uint32_t)j;
+                }
             }
         }
-        if (lane < k) store_slot(o_nbr, o_eid, o_ts, out0 + lane, rec[lo + idx]);
+        if (live && sub < k) {
+            TaserRec r = pad;
+            if (shuffle) r = rec[lo + idx];
+            else if (sub < filled) r = rec[lo + cnt - 1 - sub];
+            store_slot(o_nbr, o_eid, o_ts, out0 + sub, r);
+        }
     } else {
-        // Candidate window: lane i holds candidate i (the i-th most recent).
+        // Candidate window: lane i of the group holds candidate i (the i-th most recent).
         const int c = (int)(cnt < m ? cnt : m);
         TaserRec mine = pad;
         uint64_t w = 0;
-        if (lane < c) {
-            mine = rec[lo + cnt - 1 - lane];
+        if (sub < c) {
+            mine = rec[lo + cnt - 1 - sub];
             w = edge_weight[mine.eid];
         }
-        if (c <= k) {
-            filled = c;
-            if (lane < k) store_slot(o_nbr, o_eid, o_ts, out0 + lane, mine);
-        } else {
-            filled = k;
+        const bool draw = c > k;
+        filled = draw ? k : c;
+        if (!draw && live && sub < k) store_slot(o_nbr, o_eid, o_ts, out0 + sub, mine);
+        if (__ballot(draw)) {
             uint64_t u = 0;
-            if (lane < k) u = draw64(seed_lo, seed_hi, hop, (uint64_t)q, (uint32_t)lane);
+            if (draw && sub < k) u = draw64(seed_lo, seed_hi, hop, (uint64_t)q, (uint32_t)sub);
             for (int j = 0; j < k; ++j) {
-                uint64_t run = w;   // inclusive wave prefix sum of the remaining weights
+                uint64_t run = w;   // inclusive prefix sum of the remaining weights inside the group
 #pragma unroll
-                for (int d = 1; d < kWave; d <<= 1) {
-                    const uint32_t lo32 = __shfl_up((uint32_t)run, d, kWave);
-                    const uint32_t hi32 = __shfl_up((uint32_t)(run >> 32), d, kWave);
-                    if (lane >= d) run += ((uint64_t)hi32 << 32) | lo32;
+                for (int d = 1; d < G; d <<= 1) {
+                    const uint32_t lo32 = __shfl_up((uint32_t)run, d, G);
+                    const uint32_t hi32 = __shfl_up((uint32_t)(run >> 32), d, G);
+                    if (sub >= d) run += ((uint64_t)hi32 << 32) | lo32;
                 }
-                const uint64_t total = bcast64(run, kWave - 1);
-                const uint64_t x = __umul64hi(bcast64(u, j), total);
-                const uint64_t above = __ballot(run > x);
+                const uint64_t total = group_get64<G>(run, G - 1);
+                const uint64_t x = __umul64hi(group_get64<G>(u, j), total);
+                const uint64_t above = group_bits<G>(__ballot(draw && run > x), group);
                 const int pick = __ffsll((long long)above) - 1;
-                if (lane == pick) {
+                if (draw && sub == pick) {
                     store_slot(o_nbr, o_eid, o_ts, out0 + j, mine);
                     w = 0;
                 }
             }
         }
     }
-    if (lane == 0) o_count[q] = filled;
+    if (live && sub == 0) o_count[q] = filled;
+}
+
+template <int POLICY, int G>
+void launch_hop_g(const taser_tcsr* g, const int32_t* roots, const int64_t* times, int64_t n, int k,
+                  uint64_t seed, uint32_t hop, int m, const uint32_t* edge_weight, const taser_hop_out& o,
+                  hipStream_t stream) {
+    constexpr int roots_per_block = (kThreads / kWave) * (kWave / G);
+    const unsigned grid = (unsigned)((n + roots_per_block - 1) / roots_per_block);
+    hipLaunchKernelGGL((sample_hop_kernel<POLICY, G>), dim3(grid), dim3(kThreads), 0, stream, g->indptr, g->rec, roots,
+                       times, n, g->num_nodes, k, (uint32_t)seed, (uint32_t)(seed >> 32), hop, m, edge_weight, o.nbr,
+                       o.eid, o.ts, o.count);
 }
 
 template <int POLICY>
 void launch_hop(const taser_tcsr* g, const int32_t* roots, const int64_t* times, int64_t n, int k,
                 uint64_t seed, uint32_t hop, int m, const uint32_t* edge_weight,
                 const taser_hop_out& o, hipStream_t stream) {
-    const unsigned grid = (unsigned)((n + kRootsPerBlock - 1) / kRootsPerBlock);
     static const char* const names[3] = {"sample_hop_recent", "sample_hop_uniform", "sample_hop_weighted"};
     TaserProfileSpan span(stream, names[POLICY]);
-    hipLaunchKernelGGL(sample_hop_kernel<POLICY>, dim3(grid), dim3(kRootsPerBlock * kWave), 0, stream,
-                       g->indptr, g->rec, roots, times, n, g->num_nodes, k, (uint32_t)seed, (uint32_t)(seed >> 32),
-                       hop, m, edge_weight, o.nbr, o.eid, o.ts, o.count);
+    const int lanes = (POLICY == TASER_WEIGHTED && m > k) ? m : k;   // lanes a root needs
+    if (lanes <= 16) launch_hop_g<POLICY, 16>(g, roots, times, n, k, seed, hop, m, edge_weight, o, stream);
+    else if (lanes <= 32) launch_hop_g<POLICY, 32>(g, roots, times, n, k, seed, hop, m, edge_weight, o, stream);
+    else launch_hop_g<POLICY, 64>(g, roots, times, n, k, seed, hop, m, edge_weight, o, stream);
 }
 
 }  // namespace
