@@ -265,7 +265,7 @@ def main():
         "metric": "sampled temporal neighbors/sec + gather GB/s (% of HBM peak), 2-hop 10x10",
         "value": round(value, 1), "unit": "neighbors/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int64+bytes", "data": "synthetic",
+        "dtype": "int64", "data": "synthetic",
         "config": {"workload": w.name + ("" if args.edges is None else f" (reduced to {w.num_edges} events)"),
                    "events": w.num_edges, "nodes": w.num_nodes, "roots_per_batch": R, "fanout": [k] * hops,
                    "policy": ["recent", "uniform", "weighted"][policy], "edge_row_bytes": edge_rb,

@@ -1,0 +1,119 @@
+"""The largest workload (GDELT-shaped: 191 M events, 382 M T-CSR entries, 73 GB edge
+table in device memory) at full size, in the launch configuration bench.py times:
+the oracle recomputes a sample of the outputs one by one, and properties that hold
+at any size are checked on all of them."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2402_05396_amd as T
+from paper_2402_05396_amd import workloads as W
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(600)]
+THREADS = min(16, oracle.max_threads())
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def test_c5_full_size_sampled_parity_and_properties():
+    free, _ = torch.cuda.mem_get_info()
+    if free < 120 * 2 ** 30:
+        pytest.skip("needs ~110 GB of free device memory")
+    w = W.make(5, num_batches=2)
+    n_entries = w.src.shape[0]
+    assert n_entries == 382_000_000
+    g = T.tcsr_build(dev(w.src), dev(w.dst), dev(w.ts), dev(w.eid), w.num_nodes)
+    print("graph built", flush=True)
+
+    # ---- T-CSR: structure checks on the device + a sample of whole lists against the raw events
+    indptr, nbr, ts, eid = T.tcsr_view(g)
+    deg = torch.bincount(dev(w.src).long(), minlength=w.num_nodes)
+    assert torch.equal(indptr[1:] - indptr[:-1], deg) and int(indptr[0]) == 0 and int(indptr[-1]) == n_entries
+    seg = torch.repeat_interleave(torch.arange(w.num_nodes, device="cuda"), deg)        # owner of every entry
+    same = seg[1:] == seg[:-1]
+    assert bool(((ts[1:] >= ts[:-1]) | ~same).all())                                    # time-sorted inside every list
+    ev = dev(w.ts[::2])                                                                 # event time by edge id
+    assert torch.equal(ev[eid.long()], ts)                                              # records kept together
+    del seg, same, deg
+    indptr_h = indptr.cpu().numpy()
+    rng = np.random.default_rng(0)
+    for v in rng.integers(0, w.num_nodes, 6):
+        sel = np.flatnonzero(w.src == v)                                                # input order = (ts, position) order
+        lo, hi = indptr_h[v], indptr_h[v + 1]
+        assert hi - lo == sel.shape[0]
+        assert np.array_equal(nbr[lo:hi].cpu().numpy(), w.dst[sel])
+        assert np.array_equal(eid[lo:hi].cpu().numpy(), w.eid[sel])
+        assert np.array_equal(ts[lo:hi].cpu().numpy(), w.ts[sel])
+    del nbr, ts, eid, indptr
+    print("T-CSR checked", flush=True)
+
+    # ---- sampler on a whole batch (12 000 roots, 2 hops x 10, most recent)
+    roots, times = w.batches[0]
+    k = w.k
+    got = T.sample_temporal(g, dev(roots), dev(times), k, 2, T.RECENT, 42)
+    torch.cuda.synchronize()
+    # properties on every output: strictly earlier than the query, a real event of the root, padding after count
+    u_ev, v_ev = dev(w.src[::2]), dev(w.dst[::2])
+    q_node = [dev(roots), got[0]["nbr"].reshape(-1)]
+    q_time = [dev(times), got[0]["ts"].reshape(-1)]
+    for h in range(2):
+        o = got[h]
+        valid = o["eid"] >= 0
+        slot = torch.arange(k, device="cuda")[None, :]
+        assert torch.equal(valid, slot < o["count"][:, None])
+        assert bool((o["ts"] < q_time[h][:, None])[valid].all())
+        e = o["eid"].clamp(min=0).long()
+        root = q_node[h][:, None].expand(-1, k)
+        fwd = (u_ev[e] == root) & (v_ev[e] == o["nbr"])
+        bwd = (v_ev[e] == root) & (u_ev[e] == o["nbr"])
+        assert bool(((fwd | bwd) & (ev[e] == o["ts"]))[valid].all())
+        assert bool((o["ts"][:, :-1] >= o["ts"][:, 1:])[valid[:, 1:]].all())             # most recent first
+        assert bool((o["nbr"][~valid] == -1).all()) and bool((o["ts"][~valid] == 0).all())
+    # the oracle, one root at a time (linear scans of the raw lists), for a sample of roots of both hops
+    g_ref = oracle.tcsr_build(w.src, w.dst, w.ts, w.eid, w.num_nodes, THREADS)
+    print("oracle graph built", flush=True)
+    n0 = 300
+    ref = oracle.sample_temporal(g_ref, roots[:n0], times[:n0], k, 2, oracle.RECENT, 42, threads=THREADS)
+    for h in range(2):
+        for f in ("nbr", "eid", "ts", "count"):
+            assert np.array_equal(got[h][f][:n0 * k ** h].cpu().numpy(), ref[h][f]), (h, f)
+    pick = rng.integers(0, roots.shape[0] * k, 200)                                     # scattered second-hop roots
+    r2 = oracle.sample_hop(g_ref, got[0]["nbr"].reshape(-1)[pick].cpu().numpy(), got[0]["ts"].reshape(-1)[pick].cpu().numpy(),
+                           k, oracle.RECENT, 42, 1, threads=THREADS)
+    for f in ("nbr", "eid", "ts", "count"):
+        assert np.array_equal(got[1][f][pick].cpu().numpy(), r2[f]), f
+    del g_ref
+    print("sampler checked", flush=True)
+
+    # ---- gathers, as bench.py issues them
+    table = W.procedural_table_torch(w.edge_seed, w.num_edges, w.edge_dim, torch.float16, 192, "cuda")[:, :w.edge_dim]
+    eids = torch.cat([got[0]["eid"].reshape(-1), got[1]["eid"].reshape(-1)])
+    edge_out = T.gather_features(table, eids)
+    rows = rng.integers(0, eids.numel(), 20000)
+    e_np = eids[rows].cpu().numpy()
+    want = W.procedural_rows(w.edge_seed, np.maximum(e_np, 0), w.edge_dim, np.float16)
+    want[e_np < 0] = 0
+    assert edge_out[rows].cpu().numpy().tobytes() == want.tobytes()
+
+    node_host = torch.from_numpy(w.node_feat).pin_memory()
+    cap = int(w.cache_ratio * w.num_nodes)
+    hot = torch.from_numpy(np.ascontiguousarray(w.notes["hot_order"][:cap]))
+    cache = T.cache_init(node_host, cap, hot, staging_rows=w.num_nodes - cap)
+    T.cache_tune(cache, stage_blocks=16, refresh_before_gather=True)
+    ids = torch.cat([dev(roots), got[0]["nbr"].reshape(-1), got[1]["nbr"].reshape(-1)])
+    hm = torch.zeros(2, dtype=torch.int64, device="cuda")
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    ready, staged = torch.cuda.Event(), torch.cuda.Event()
+    ready.record(main)
+    side.wait_event(ready)
+    T.cache_prefetch(cache, ids, hit_miss=hm, stream=side)
+    staged.record(side)
+    main.wait_event(staged)
+    node_out = T.cache_gather(cache, ids, stream=main)
+    torch.cuda.synchronize()
+    ids_np = ids.cpu().numpy()
+    assert node_out.cpu().numpy().tobytes() == oracle.gather(w.node_feat, ids_np, threads=THREADS).tobytes()
+    assert tuple(hm.tolist()) == oracle.cache_hits(hot.numpy(), w.num_nodes, ids_np)
