@@ -165,3 +165,22 @@ def cache_hits(resident, rows, ids):
     _load().oracle_cache_hits(_p(resident), ctypes.c_int64(resident.shape[0]),
                               ctypes.c_int64(rows), _p(ids), ctypes.c_int64(ids.shape[0]), _p(hm))
     return int(hm[0]), int(hm[1])
+
+
+def cache_count(ids, rows, Q):
+    """Q[id] += 1 for every valid request (in place; Q is uint32[rows])."""
+    ids = _c(ids, np.int32).ravel()
+    assert Q.dtype == np.uint32 and Q.flags.c_contiguous and Q.shape[0] == rows
+    _load().oracle_cache_count(_p(ids), ctypes.c_int64(ids.shape[0]), ctypes.c_int64(rows), _p(Q))
+
+
+def cache_epoch_end(Q, resident, min_overlap):
+    """Returns (replaced, overlap, new_resident); clears Q in place."""
+    resident = _c(resident, np.int32)
+    assert Q.dtype == np.uint32 and Q.flags.c_contiguous
+    new = np.empty_like(resident)
+    overlap = ctypes.c_int64()
+    rep = _load().oracle_cache_epoch_end(_p(Q), ctypes.c_int64(Q.shape[0]), _p(resident),
+                                         ctypes.c_int64(resident.shape[0]), ctypes.c_int64(min_overlap),
+                                         _p(new), ctypes.byref(overlap))
+    return bool(rep), int(overlap.value), new

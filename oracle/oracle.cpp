@@ -349,4 +349,38 @@ void oracle_cache_hits(const int32_t* resident, int64_t capacity, int64_t rows,
     hit_miss[1] = misses;
 }
 
+/* Access counting (paper Alg. 3: Q[e] <- Q[e] + 1 for every read request e).
+ * Requests with an id outside [0, rows) are not counted. */
+void oracle_cache_count(const int32_t* ids, int64_t n, int64_t rows, uint32_t* Q) {
+    for (int64_t i = 0; i < n; ++i)
+        if (ids[i] >= 0 && ids[i] < rows) Q[ids[i]] += 1;
+}
+
+/* End of an epoch (paper Alg. 3 and Sec. 3.4): Q_topk = the `capacity` most
+ * frequently requested rows of the epoch (ties: the smaller id wins). If fewer
+ * than `min_overlap` of them are currently resident, the cache content becomes
+ * Q_topk; otherwise it stays. Either way Q is cleared for the next epoch.
+ * new_resident receives the resident ids after the step (Q_topk in ascending
+ * id order when replaced, the old list unchanged otherwise); *overlap receives
+ * |resident n Q_topk|. Returns 1 if the content was replaced, else 0. */
+int oracle_cache_epoch_end(uint32_t* Q, int64_t rows, const int32_t* resident, int64_t capacity,
+                           int64_t min_overlap, int32_t* new_resident, int64_t* overlap) {
+    std::vector<int32_t> order((size_t)rows);
+    for (int64_t i = 0; i < rows; ++i) order[(size_t)i] = (int32_t)i;
+    std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        if (Q[a] != Q[b]) return Q[a] > Q[b];
+        return a < b;
+    });
+    std::vector<int32_t> topk(order.begin(), order.begin() + capacity);
+    std::sort(topk.begin(), topk.end());
+    int64_t both = 0;
+    for (int64_t i = 0; i < capacity; ++i)
+        if (std::binary_search(topk.begin(), topk.end(), resident[i])) ++both;
+    *overlap = both;
+    const int replace = both < min_overlap;
+    for (int64_t i = 0; i < capacity; ++i) new_resident[i] = replace ? topk[(size_t)i] : resident[i];
+    for (int64_t i = 0; i < rows; ++i) Q[i] = 0;
+    return replace;
+}
+
 }  // extern "C"

@@ -65,12 +65,31 @@ __global__ __launch_bounds__(kThreads) void inspect_kernel(const int32_t* __rest
         any_or |= __shfl_xor(any_or, d, kWave);
         all_and &= __shfl_xor(all_and, d, kWave);
     }
+    // one set of atomics per block, not per wave: they all land on the same four words
+    __shared__ unsigned long long w_or[kWaves], w_and[kWaves];
+    __shared__ int w_bad[kWaves], w_unsorted[kWaves];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const unsigned long long any_bad = __ballot(bad), any_unsorted = __ballot(unsorted);
-    if ((threadIdx.x & (kWave - 1)) == 0) {
-        if (any_bad) atomicOr(&info[0], 1ull);
-        if (any_unsorted) atomicOr(&info[1], 1ull);
-        atomicOr(&info[2], any_or);
-        atomicAnd(&info[3], all_and);
+    if (lane == 0) {
+        w_or[wave] = any_or;
+        w_and[wave] = all_and;
+        w_bad[wave] = any_bad != 0;
+        w_unsorted[wave] = any_unsorted != 0;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long o = 0, a = ~0ull;
+        int b = 0, u = 0;
+        for (int w = 0; w < kWaves; ++w) {
+            o |= w_or[w];
+            a &= w_and[w];
+            b |= w_bad[w];
+            u |= w_unsorted[w];
+        }
+        if (b) atomicOr(&info[0], 1ull);
+        if (u) atomicOr(&info[1], 1ull);
+        atomicOr(&info[2], o);
+        atomicAnd(&info[3], a);
     }
 }
 
@@ -305,7 +324,7 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
         TASER_HIP_TRY(d_info.alloc(sizeof(info)));
         TASER_HIP_TRY(hipMemcpyAsync(d_info.p, info, sizeof(info), hipMemcpyHostToDevice, stream));
         unsigned grid = blocks_for(n, kThreads);
-        if (grid > 4096) grid = 4096;
+        if (grid > 1024) grid = 1024;
         {
             TaserProfileSpan span(stream, "tcsr_inspect");
             hipLaunchKernelGGL(inspect_kernel, dim3(grid), dim3(kThreads), 0, stream, src, ts, n, num_nodes,

@@ -431,3 +431,69 @@ def test_cache_residents_and_hit_accounting():
     firsts = np.array([oracle.cache_random_residents(50, 1, seed=s)[0] for s in range(20000)])
     obs = np.bincount(firsts, minlength=50)
     assert (((obs - 400) ** 2) / 400).sum() < stats.chi2.ppf(1 - 1e-4, 49)
+
+
+# --------------------------------------------------------------------------- cache maintenance (Alg. 3)
+def test_cache_counting_equals_bincount():
+    rng = np.random.default_rng(4)
+    rows = 300
+    ids = rng.integers(-2, rows + 3, 20000).astype(np.int32)
+    Q = np.zeros(rows, np.uint32)
+    oracle.cache_count(ids, rows, Q)
+    oracle.cache_count(ids[:100], rows, Q)
+    ok = (ids >= 0) & (ids < rows)
+    want = np.bincount(ids[ok], minlength=rows) + np.bincount(ids[:100][ok[:100]], minlength=rows)
+    assert np.array_equal(Q, want.astype(np.uint32))
+
+
+def test_cache_epoch_end_is_topk_with_threshold():
+    """Q_topk by numpy (stable argsort of -count: ties keep the smaller id), overlap by set
+    intersection, replacement only below the threshold, Q cleared either way."""
+    rng = np.random.default_rng(6)
+    rows, cap = 500, 60
+    for trial in range(20):
+        Q = rng.integers(0, 8, rows).astype(np.uint32)            # heavy ties
+        if trial == 0:
+            Q[:] = 0                                                # nothing was requested
+        resident = rng.permutation(rows)[:cap].astype(np.int32)
+        topk = np.sort(np.argsort(-Q.astype(np.int64), kind="stable")[:cap])
+        overlap = len(set(topk.tolist()) & set(resident.tolist()))
+        for thr in (0, overlap, overlap + 1, cap):
+            q = Q.copy()
+            rep, ov, new = oracle.cache_epoch_end(q, resident, thr)
+            assert ov == overlap and rep == (overlap < thr)
+            assert np.array_equal(new, topk if rep else resident)
+            assert not q.any()
+        # brute force: every kept row is requested at least as often as every dropped row
+        kept = np.zeros(rows, bool)
+        kept[topk] = True
+        assert Q[kept].min() >= Q[~kept].max()
+
+
+def test_cache_policy_converges_on_a_stationary_stream():
+    """With a stationary access distribution the previous epoch's top-k is close to the best
+    possible content (Sec. 3.4, Fig. 3b): after one refresh the hit rate is within a few percent
+    of the cache that knows the epoch's frequencies in advance, and it grows with the cache size."""
+    rng = np.random.default_rng(8)
+    rows, per_epoch = 2000, 100000
+    p = 1.0 / np.arange(1, rows + 1)
+    p /= p.sum()
+    perm = rng.permutation(rows)
+    rates = []
+    for frac in (0.1, 0.2, 0.3):
+        cap = int(frac * rows)
+        resident = oracle.cache_random_residents(rows, cap, seed=3)
+        Q = np.zeros(rows, np.uint32)
+        hit_rate = []
+        for epoch in range(3):
+            ids = perm[rng.choice(rows, per_epoch, p=p)].astype(np.int32)
+            h, m = oracle.cache_hits(resident, rows, ids)
+            hit_rate.append(h / (h + m))
+            best = np.sort(np.bincount(ids, minlength=rows))[::-1][:cap].sum() / per_epoch   # knows this epoch
+            oracle.cache_count(ids, rows, Q)
+            _, _, resident = oracle.cache_epoch_end(Q, resident, cap)                         # always below cap+...: refresh
+            if epoch >= 1:
+                assert best - hit_rate[-1] < 0.03
+        assert hit_rate[1] > hit_rate[0] + 0.2
+        rates.append(hit_rate[-1])
+    assert rates[0] < rates[1] < rates[2]
