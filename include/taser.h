@@ -219,6 +219,32 @@ int taser_cache_gather(taser_cache* c, const int32_t* ids, int64_t n, void* out,
  *                 Default off. Never changes results. */
 int taser_cache_tune(taser_cache* c, int32_t stage_blocks, int32_t refresh_before_gather);
 
+/* ---------------------------------------------------------------------------
+ * Cache maintenance (Alg. 3; Sec. 3.4): count how often every row is requested
+ * and, at the end of an epoch, swap the cache content for the most requested
+ * rows if too few of them are resident.
+ *
+ * taser_cache_count_accesses(enable != 0): from now on every lookup/prefetch
+ * adds 1 to the counter of each requested row with a valid id (hit or miss).
+ * The counters (uint32 per row, device memory, zeroed when first enabled) are
+ * allocated on first use; enable == 0 pauses counting and keeps them.
+ *
+ * taser_cache_access_counts copies the counters into `counts`
+ * (device uint32[rows], caller-allocated), ordered on `hip_stream`.
+ *
+ * taser_cache_epoch_end: Q_topk = the capacity_rows rows with the largest
+ * counters (ties: the smaller id). *overlap (host, may be NULL) receives how
+ * many of them are resident. If that is below min_overlap the cache content is
+ * replaced by Q_topk (slots in ascending id order: rows re-read from the host
+ * table, index rebuilt) and *replaced (host, may be NULL) is set to 1, else 0.
+ * The counters are zeroed either way. Synchronizes `hip_stream`; no lookup on
+ * this handle may be in flight. TASER_E_ARG if counting was never enabled.
+ * ------------------------------------------------------------------------- */
+int taser_cache_count_accesses(taser_cache* c, int32_t enable, void* hip_stream);
+int taser_cache_access_counts(const taser_cache* c, uint32_t* counts, void* hip_stream);
+int taser_cache_epoch_end(taser_cache* c, int64_t min_overlap, int64_t* overlap, int32_t* replaced,
+                          void* hip_stream);
+
 /* Copies the resident row ids (slot order) to host int32[capacity_rows]. */
 int taser_cache_residents(const taser_cache* c, int32_t* resident_ids_host);
 

@@ -19,7 +19,8 @@ INPUT_ON_DEVICE = 1
 MAX_K, MAX_M, MAX_HOPS = 64, 64, 3
 
 EXPORTS = ("taser_tcsr_build", "taser_tcsr_size", "taser_tcsr_view", "taser_tcsr_free", "taser_sample_temporal",
-           "taser_gather_features", "taser_cache_init", "taser_cache_lookup", "taser_cache_prefetch", "taser_cache_gather", "taser_cache_tune", "taser_cache_residents",
+           "taser_gather_features", "taser_cache_init", "taser_cache_lookup", "taser_cache_prefetch", "taser_cache_gather", "taser_cache_tune", "taser_cache_count_accesses", "taser_cache_access_counts",
+           "taser_cache_epoch_end", "taser_cache_residents",
            "taser_cache_free", "taser_profile_begin", "taser_profile_end", "taser_last_error")
 
 
@@ -63,6 +64,9 @@ def lib():
         L.taser_cache_prefetch.argtypes = [vp, vp, i64, vp, vp]
         L.taser_cache_gather.argtypes = [vp, vp, i64, vp, vp]
         L.taser_cache_tune.argtypes = [vp, i32, i32]
+        L.taser_cache_count_accesses.argtypes = [vp, i32, vp]
+        L.taser_cache_access_counts.argtypes = [vp, vp, vp]
+        L.taser_cache_epoch_end.argtypes = [vp, i64, ctypes.POINTER(i64), ctypes.POINTER(i32), vp]
         L.taser_cache_residents.argtypes = [vp, vp]
         L.taser_cache_free.argtypes = [vp]
         L.taser_cache_free.restype = None
@@ -277,6 +281,26 @@ def cache_gather(c, ids, out=None, stream=None):
 def cache_tune(c, stage_blocks=0, refresh_before_gather=False):
     """taser_cache_tune."""
     _check(lib().taser_cache_tune(c.handle, stage_blocks, 1 if refresh_before_gather else 0))
+
+
+def cache_count_accesses(c, enable=True, stream=None):
+    """taser_cache_count_accesses."""
+    _check(lib().taser_cache_count_accesses(c.handle, 1 if enable else 0, _stream(stream)))
+
+
+def cache_access_counts(c, stream=None):
+    """taser_cache_access_counts -> device int32 tensor holding the uint32 counters."""
+    out = torch.empty(c.host_table.shape[0], dtype=torch.int32, device="cuda")
+    _check(lib().taser_cache_access_counts(c.handle, _ptr(out), _stream(stream)))
+    return out
+
+
+def cache_epoch_end(c, min_overlap, stream=None):
+    """taser_cache_epoch_end -> (replaced, overlap)."""
+    overlap, replaced = ctypes.c_int64(), ctypes.c_int32()
+    _check(lib().taser_cache_epoch_end(c.handle, min_overlap, ctypes.byref(overlap), ctypes.byref(replaced),
+                                       _stream(stream)))
+    return bool(replaced.value), int(overlap.value)
 
 
 def cache_residents(c):

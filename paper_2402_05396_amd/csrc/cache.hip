@@ -21,10 +21,12 @@
 //      zero rows, or straight from host memory for requests that found the
 //      miss table full.
 // Which rows are resident only changes where bytes come from, never the bytes.
+#include <cstdio>
 #include <new>
 #include <vector>
 
 #include "gather_kernel.h"
+#include "scan_kernels.h"
 #include "taser_internal.h"
 
 namespace {
@@ -34,6 +36,7 @@ constexpr int32_t kEmpty = -1;
 constexpr int32_t kLocZero = -1;                   // request with a negative id
 constexpr int32_t kLocHost = INT32_MIN;            // read the host row directly
 constexpr int kMaxMissProbes = 128;
+constexpr int kTallySlots = 1024;                 // per-block LDS table of the access counting
 constexpr uint32_t kTagCache = 0x43414348u;        // hop tag of the residency shuffle
 
 __host__ __device__ inline uint32_t hash_id(int32_t id, uint32_t mask) {
@@ -67,6 +70,9 @@ struct taser_cache {
     int stage_blocks;                // width of the host -> staging copy, in 256-thread blocks
     bool refresh_before_gather;      // see rewrite_kernel
     std::vector<int32_t>* residents;   // host copy, slot order
+    int32_t* resident_dev;             // device copy of the same
+    uint32_t* access_count;            // device [rows] or null: requests per row since the last epoch end
+    bool counting;
 };
 
 namespace {
@@ -82,13 +88,39 @@ __global__ __launch_bounds__(kThreads) void fill_kernel(int32_t* a, uint32_t n, 
 __global__ __launch_bounds__(kThreads) void classify_kernel(
     const int32_t* __restrict__ ids, int64_t n, int64_t rows, const int32_t* __restrict__ hash_key,
     const int32_t* __restrict__ hash_slot, uint32_t hash_mask, int32_t* miss_key, uint32_t miss_size,
-    int32_t* __restrict__ loc, unsigned long long* hit_miss) {
+    int32_t* __restrict__ loc, unsigned long long* hit_miss, uint32_t* access_count) {
     __shared__ uint32_t block_hits[kThreads / kWave], block_misses[kThreads / kWave];
+    // Access counting: a block first sums its own requests per id in a small LDS
+    // hash table and adds each distinct id to the global counter once, so a row
+    // that a tenth of all requests name costs one global atomic per block.
+    __shared__ int32_t tally_key[kTallySlots];
+    __shared__ uint32_t tally_count[kTallySlots];
+    if (access_count) {
+        for (int s = threadIdx.x; s < kTallySlots; s += kThreads) {
+            tally_key[s] = kEmpty;
+            tally_count[s] = 0;
+        }
+        __syncthreads();
+    }
     uint32_t hits = 0, misses = 0;
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kThreads) {
         const int32_t id = ids[i];
         int32_t where = kLocZero;
         if (id >= 0 && id < rows) {
+            if (access_count) {
+                uint32_t s = hash_id(id, kTallySlots - 1);
+                bool done = false;
+                for (int probe = 0; probe < 8 && !done; ++probe) {
+                    int32_t key = tally_key[s];
+                    if (key == kEmpty) key = atomicCAS(&tally_key[s], kEmpty, id);
+                    if (key == kEmpty || key == id) {
+                        atomicAdd(&tally_count[s], 1u);
+                        done = true;
+                    }
+                    s = (s + 1) & (kTallySlots - 1);
+                }
+                if (!done) atomicAdd(&access_count[id], 1u);   // table crowded: count directly
+            }
             uint32_t h = hash_id(id, hash_mask);
             int32_t slot = -1;
             for (;;) {                               // the table is never full: the loop ends at an empty key
@@ -115,6 +147,11 @@ __global__ __launch_bounds__(kThreads) void classify_kernel(
             }
         }
         loc[i] = where;
+    }
+    if (access_count) {
+        __syncthreads();
+        for (int s = threadIdx.x; s < kTallySlots; s += kThreads)
+            if (tally_key[s] != kEmpty) atomicAdd(&access_count[tally_key[s]], tally_count[s]);
     }
     if (!hit_miss) return;
     for (int d = kWave / 2; d > 0; d >>= 1) {
@@ -224,6 +261,61 @@ struct CacheSource {
     }
 };
 
+// ---- epoch-end maintenance (Alg. 3): the `capacity` most requested rows -----
+// Histogram of one byte of the counts, over the rows whose higher bytes equal
+// `prefix` (radix select, most significant byte first).
+__global__ __launch_bounds__(kThreads) void count_digit_hist_kernel(const uint32_t* __restrict__ count, int64_t rows,
+                                                                    int shift, uint32_t prefix, uint32_t* hist) {
+    __shared__ uint32_t bins[256];
+    bins[threadIdx.x] = 0;
+    __syncthreads();
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < rows; i += (int64_t)gridDim.x * kThreads) {
+        const uint32_t v = count[i];
+        if (shift == 24 || (v >> (shift + 8)) == prefix) atomicAdd(&bins[(v >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (bins[threadIdx.x]) atomicAdd(&hist[threadIdx.x], bins[threadIdx.x]);
+}
+
+// flag[i] = 1 where the predicate holds (MODE 0: count == t; MODE 1: count > t,
+// or count == t and fewer than `ties` equal rows precede row i).
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void flag_rows_kernel(const uint32_t* __restrict__ count, int64_t rows, uint32_t t,
+                                                             const uint32_t* __restrict__ tie_rank, uint32_t ties,
+                                                             uint32_t* __restrict__ flag) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= rows) return;
+    const uint32_t v = count[i];
+    if (MODE == 0) flag[i] = v == t;
+    else flag[i] = (v > t) || (v == t && tie_rank[i] < ties);
+}
+
+// Writes the selected ids in ascending order (position = exclusive scan of the
+// flags) and counts how many of them are resident already.
+__global__ __launch_bounds__(kThreads) void emit_selected_kernel(const uint32_t* __restrict__ count, int64_t rows, uint32_t t,
+                                                                 const uint32_t* __restrict__ tie_rank, uint32_t ties,
+                                                                 const uint32_t* __restrict__ position,
+                                                                 const int32_t* __restrict__ hash_key, uint32_t hash_mask,
+                                                                 int32_t* __restrict__ selected, unsigned long long* overlap) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    bool resident = false;
+    if (i < rows) {
+        const uint32_t v = count[i];
+        if ((v > t) || (v == t && tie_rank[i] < ties)) {
+            selected[position[i]] = (int32_t)i;
+            uint32_t h = hash_id((int32_t)i, hash_mask);
+            for (;;) {
+                const int32_t key = hash_key[h];
+                if (key == (int32_t)i) { resident = true; break; }
+                if (key == kEmpty) break;
+                h = (h + 1) & hash_mask;
+            }
+        }
+    }
+    const unsigned long long both = __ballot(resident);
+    if ((threadIdx.x & (kWave - 1)) == 0 && both) atomicAdd(overlap, (unsigned long long)__popcll(both));
+}
+
 // Philox4x32-10 on the host, for the default residency draw only.
 uint64_t host_draw64(uint64_t seed, uint32_t hop, uint64_t root, uint32_t slot) {
     uint32_t c[4] = {(uint32_t)root, (uint32_t)(root >> 32), slot, hop};
@@ -246,14 +338,48 @@ uint32_t pow2_at_least(uint64_t x) {
 
 void destroy(taser_cache* c) {
     if (!c) return;
-    (void)hipFree(c->cache_rows);
-    (void)hipFree(c->hash_key);
-    (void)hipFree(c->hash_slot);
-    (void)hipFree(c->stage_rows);
-    (void)hipFree(c->miss_key);
-    (void)hipFree(c->loc);
+    void* const owned[] = {c->cache_rows, c->hash_key, c->hash_slot, c->stage_rows, c->miss_key,
+                           c->loc, c->resident_dev, c->access_count};
+    int at = 0;
+    for (void* p : owned) {
+        const hipError_t e = p ? hipFree(p) : hipSuccess;
+        if (e != hipSuccess) fprintf(stderr, "taser: cache free: buffer %d (%p): %s\n", at, p, hipGetErrorString(e));
+        ++at;
+    }
+    (void)hipGetLastError();   // a failed free must not poison the caller's next HIP call
     delete c->residents;
     delete c;
+}
+
+// Makes `*c->residents` (slot order) the cache content: builds the id -> slot hash
+// on the host, uploads it, and fills the cache rows by a gather straight out of
+// host memory. Synchronizes the stream.
+int install_residents(taser_cache* c, hipStream_t stream) {
+    const std::vector<int32_t>& res = *c->residents;
+    const uint32_t hash_size = c->hash_mask + 1;
+    std::vector<int32_t> h_key, h_slot;
+    try {
+        h_key.assign(hash_size, kEmpty);
+        h_slot.assign(hash_size, -1);
+    } catch (const std::bad_alloc&) {
+        return taser_fail(TASER_E_OOM, "cache: host allocation failed");
+    }
+    for (int64_t s = 0; s < c->capacity; ++s) {
+        uint32_t h = hash_id(res[(size_t)s], c->hash_mask);
+        while (h_key[h] != kEmpty) h = (h + 1) & c->hash_mask;
+        h_key[h] = res[(size_t)s];
+        h_slot[h] = (int32_t)s;
+    }
+    TASER_HIP_TRY(hipMemcpyAsync(c->hash_key, h_key.data(), (size_t)hash_size * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+    TASER_HIP_TRY(hipMemcpyAsync(c->hash_slot, h_slot.data(), (size_t)hash_size * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+    if (c->capacity > 0) {
+        TASER_HIP_TRY(hipMemcpyAsync(c->resident_dev, res.data(), (size_t)c->capacity * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+        const int rc = taser_launch_gather(c->host_rows, c->rows, c->row_bytes, c->pitch_bytes, c->resident_dev, c->capacity,
+                                           c->cache_rows, stream);
+        if (rc != TASER_OK) return rc;
+    }
+    TASER_HIP_TRY(hipStreamSynchronize(stream));   // the host vectors above must outlive the copies
+    return TASER_OK;
 }
 
 }  // namespace
@@ -326,16 +452,8 @@ extern "C" int taser_cache_init(const void* host_table, int64_t rows, int32_t ro
         return taser_fail(TASER_E_OOM, "cache_init: host allocation failed");
     }
 
-    // ---- hash table id -> slot, built on the host and uploaded
     const uint32_t hash_size = pow2_at_least((uint64_t)(capacity_rows > 8 ? capacity_rows : 8) * 2);
     c->hash_mask = hash_size - 1;
-    std::vector<int32_t> h_key(hash_size, kEmpty), h_slot(hash_size, -1);
-    for (int64_t s = 0; s < capacity_rows; ++s) {
-        uint32_t h = hash_id(res[(size_t)s], c->hash_mask);
-        while (h_key[h] != kEmpty) h = (h + 1) & c->hash_mask;
-        h_key[h] = res[(size_t)s];
-        h_slot[h] = (int32_t)s;
-    }
     c->miss_size = staging_rows > 0 ? pow2_at_least((uint64_t)(staging_rows > 32 ? staging_rows : 32) * 2) : 0;   // >= 64
 
 #define CACHE_TRY(expr)                                               \
@@ -343,30 +461,17 @@ extern "C" int taser_cache_init(const void* host_table, int64_t rows, int32_t ro
         hipError_t e_ = (expr);                                       \
         if (e_ != hipSuccess) { destroy(c); return taser_fail_hip(e_, #expr); } \
     } while (0)
-    int32_t* d_res = nullptr;
     CACHE_TRY(hipMalloc((void**)&c->cache_rows, (size_t)(capacity_rows > 0 ? capacity_rows : 1) * c->dev_pitch));
     CACHE_TRY(hipMalloc((void**)&c->hash_key, (size_t)hash_size * sizeof(int32_t)));
     CACHE_TRY(hipMalloc((void**)&c->hash_slot, (size_t)hash_size * sizeof(int32_t)));
-    CACHE_TRY(hipMemcpyAsync(c->hash_key, h_key.data(), (size_t)hash_size * sizeof(int32_t), hipMemcpyHostToDevice, stream));
-    CACHE_TRY(hipMemcpyAsync(c->hash_slot, h_slot.data(), (size_t)hash_size * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+    CACHE_TRY(hipMalloc((void**)&c->resident_dev, (size_t)(capacity_rows > 0 ? capacity_rows : 1) * sizeof(int32_t)));
     if (c->miss_size) {
         CACHE_TRY(hipMalloc((void**)&c->stage_rows, (size_t)c->miss_size * c->dev_pitch));
         CACHE_TRY(hipMalloc((void**)&c->miss_key, (size_t)c->miss_size * sizeof(int32_t)));
     }
-    if (capacity_rows > 0) {
-        // fill the cache: a gather of the resident rows straight out of host memory
-        CACHE_TRY(hipMalloc((void**)&d_res, (size_t)capacity_rows * sizeof(int32_t)));
-        hipError_t e = hipMemcpyAsync(d_res, res.data(), (size_t)capacity_rows * sizeof(int32_t), hipMemcpyHostToDevice, stream);
-        int rc = TASER_OK;
-        if (e != hipSuccess) rc = taser_fail_hip(e, "hipMemcpyAsync(resident ids)");
-        if (rc == TASER_OK) rc = taser_launch_gather(c->host_rows, rows, row_bytes, pitch_bytes, d_res, capacity_rows, c->cache_rows, stream);
-        e = hipStreamSynchronize(stream);
-        (void)hipFree(d_res);
-        if (rc == TASER_OK && e != hipSuccess) rc = taser_fail_hip(e, "hipStreamSynchronize");
-        if (rc != TASER_OK) { destroy(c); return rc; }
-    }
-    CACHE_TRY(hipStreamSynchronize(stream));
 #undef CACHE_TRY
+    const int rc = install_residents(c, stream);
+    if (rc != TASER_OK) { destroy(c); return rc; }
     *out = c;
     return TASER_OK;
 }
@@ -379,6 +484,7 @@ extern "C" int taser_cache_prefetch(taser_cache* c, const int32_t* ids, int64_t 
     c->prefetched_n = 0;
     if (n == 0) return TASER_OK;
     if (!ids) return taser_fail(TASER_E_ARG, "cache_prefetch: null ids");
+    taser_clear_stale_hip_error();
     hipStream_t stream = (hipStream_t)hip_stream;
     if (n > c->loc_capacity) {
         // grows only; the old buffer may still be in use by earlier work on this stream
@@ -400,7 +506,7 @@ extern "C" int taser_cache_prefetch(taser_cache* c, const int32_t* ids, int64_t 
         TaserProfileSpan span(stream, "cache_classify");
         hipLaunchKernelGGL(classify_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, ids, n, c->rows,
                            c->hash_key, c->hash_slot, c->hash_mask, c->miss_key, c->miss_size, c->loc,
-                           reinterpret_cast<unsigned long long*>(hit_miss));
+                           reinterpret_cast<unsigned long long*>(hit_miss), c->counting ? c->access_count : nullptr);
     }
     if (c->miss_size) {
         TaserProfileSpan span(stream, "cache_stage_misses");
@@ -421,6 +527,7 @@ extern "C" int taser_cache_gather(taser_cache* c, const int32_t* ids, int64_t n,
     if (n == 0) return TASER_OK;
     if (!out) return taser_fail(TASER_E_ARG, "cache_gather: null out");
     if ((uintptr_t)out & 3) return taser_fail(TASER_E_ARG, "cache_gather: out must be 4-byte aligned");
+    taser_clear_stale_hip_error();
     hipStream_t stream = (hipStream_t)hip_stream;
     const CacheSource source{c->loc, ids, c->cache_rows, c->stage_rows, c->dev_pitch, c->host_rows, c->pitch_bytes};
     const int align = taser_gather::common_alignment((uint64_t)c->row_bytes | (uint64_t)c->pitch_bytes |
@@ -453,6 +560,105 @@ extern "C" int taser_cache_lookup(taser_cache* c, const int32_t* ids, int64_t n,
     const int rc = taser_cache_prefetch(c, ids, n, hit_miss, hip_stream);
     if (rc != TASER_OK) return rc;
     return taser_cache_gather(c, ids, n, out, hip_stream);
+}
+
+extern "C" int taser_cache_count_accesses(taser_cache* c, int32_t enable, void* hip_stream) {
+    if (!c) return taser_fail(TASER_E_ARG, "cache_count_accesses: null cache");
+    taser_clear_stale_hip_error();
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (enable && !c->access_count) {
+        TASER_HIP_TRY(hipMalloc((void**)&c->access_count, (size_t)c->rows * sizeof(uint32_t)));
+        hipLaunchKernelGGL(fill_kernel, dim3((unsigned)((c->rows + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,
+                           reinterpret_cast<int32_t*>(c->access_count), (uint32_t)c->rows, 0);
+        TASER_HIP_TRY(hipGetLastError());
+    }
+    c->counting = enable != 0;
+    return TASER_OK;
+}
+
+extern "C" int taser_cache_access_counts(const taser_cache* c, uint32_t* counts, void* hip_stream) {
+    if (!c || !counts) return taser_fail(TASER_E_ARG, "cache_access_counts: null argument");
+    if (!c->access_count) return taser_fail(TASER_E_ARG, "cache_access_counts: counting was never enabled");
+    TASER_HIP_TRY(hipMemcpyAsync(counts, c->access_count, (size_t)c->rows * sizeof(uint32_t), hipMemcpyDeviceToDevice,
+                                 (hipStream_t)hip_stream));
+    return TASER_OK;
+}
+
+extern "C" int taser_cache_epoch_end(taser_cache* c, int64_t min_overlap, int64_t* overlap, int32_t* replaced,
+                                     void* hip_stream) {
+    if (!c) return taser_fail(TASER_E_ARG, "cache_epoch_end: null cache");
+    if (!c->access_count) return taser_fail(TASER_E_ARG, "cache_epoch_end: counting was never enabled");
+    taser_clear_stale_hip_error();
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const int64_t rows = c->rows, k = c->capacity;
+    const unsigned row_blocks = (unsigned)((rows + kThreads - 1) / kThreads);
+    int64_t both = k;       // with k == 0 or k == rows the top-k is what is resident
+    bool replace = false;
+    if (k > 0 && k < rows) {
+        struct Scratch {
+            uint32_t *hist = nullptr, *rank = nullptr, *pos = nullptr, *partial = nullptr;
+            int32_t* selected = nullptr;
+            unsigned long long* overlap = nullptr;
+            ~Scratch() {
+                (void)hipFree(hist); (void)hipFree(rank); (void)hipFree(pos); (void)hipFree(partial);
+                (void)hipFree(selected); (void)hipFree(overlap);
+            }
+        } w;
+        TASER_HIP_TRY(hipMalloc((void**)&w.hist, 256 * sizeof(uint32_t)));
+        TASER_HIP_TRY(hipMalloc((void**)&w.rank, (size_t)rows * sizeof(uint32_t)));
+        TASER_HIP_TRY(hipMalloc((void**)&w.pos, (size_t)rows * sizeof(uint32_t)));
+        TASER_HIP_TRY(hipMalloc((void**)&w.partial, (size_t)taser_scan::num_partials(rows) * sizeof(uint32_t)));
+        TASER_HIP_TRY(hipMalloc((void**)&w.selected, (size_t)k * sizeof(int32_t)));
+        TASER_HIP_TRY(hipMalloc((void**)&w.overlap, sizeof(unsigned long long)));
+        TaserProfileSpan span(stream, "cache_epoch_end");
+        // radix select: the count t of the k-th most requested row, most significant byte first
+        uint32_t prefix = 0;
+        int64_t above = 0;                      // rows with a count above the prefix range chosen so far
+        unsigned grid = row_blocks < 1024 ? row_blocks : 1024;
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            uint32_t hist[256];
+            hipLaunchKernelGGL(fill_kernel, dim3(1), dim3(kThreads), 0, stream, reinterpret_cast<int32_t*>(w.hist), 256u, 0);
+            hipLaunchKernelGGL(count_digit_hist_kernel, dim3(grid), dim3(kThreads), 0, stream, c->access_count, rows, shift,
+                               prefix, w.hist);
+            TASER_HIP_TRY(hipMemcpyAsync(hist, w.hist, sizeof(hist), hipMemcpyDeviceToHost, stream));
+            TASER_HIP_TRY(hipStreamSynchronize(stream));
+            int bin = 255;
+            while (bin > 0 && above + hist[bin] < k) above += hist[bin--];
+            prefix = (prefix << 8) | (uint32_t)bin;
+        }
+        const uint32_t t = prefix;              // `above` rows have a larger count
+        const uint32_t ties = (uint32_t)(k - above);   // rows with count == t that still fit, smallest ids first
+        hipLaunchKernelGGL(flag_rows_kernel<0>, dim3(row_blocks), dim3(kThreads), 0, stream, c->access_count, rows, t,
+                           (const uint32_t*)nullptr, 0u, w.rank);
+        taser_scan::exclusive_scan_u32(w.rank, rows, w.partial, stream);
+        hipLaunchKernelGGL(flag_rows_kernel<1>, dim3(row_blocks), dim3(kThreads), 0, stream, c->access_count, rows, t,
+                           (const uint32_t*)w.rank, ties, w.pos);
+        taser_scan::exclusive_scan_u32(w.pos, rows, w.partial, stream);
+        hipLaunchKernelGGL(fill_kernel, dim3(1), dim3(kThreads), 0, stream, reinterpret_cast<int32_t*>(w.overlap), 2u, 0);
+        hipLaunchKernelGGL(emit_selected_kernel, dim3(row_blocks), dim3(kThreads), 0, stream, c->access_count, rows, t,
+                           (const uint32_t*)w.rank, ties, (const uint32_t*)w.pos, c->hash_key, c->hash_mask, w.selected,
+                           w.overlap);
+        TASER_HIP_TRY(hipGetLastError());
+        unsigned long long h_both = 0;
+        TASER_HIP_TRY(hipMemcpyAsync(&h_both, w.overlap, sizeof(h_both), hipMemcpyDeviceToHost, stream));
+        TASER_HIP_TRY(hipStreamSynchronize(stream));
+        both = (int64_t)h_both;
+        replace = both < min_overlap;
+        if (replace) {
+            TASER_HIP_TRY(hipMemcpy(c->residents->data(), w.selected, (size_t)k * sizeof(int32_t), hipMemcpyDeviceToHost));
+            const int rc = install_residents(c, stream);
+            if (rc != TASER_OK) return rc;
+            c->prefetched_ids = nullptr;        // locations computed before the swap are stale
+            c->prefetched_n = 0;
+        }
+    }
+    hipLaunchKernelGGL(fill_kernel, dim3(row_blocks), dim3(kThreads), 0, stream, reinterpret_cast<int32_t*>(c->access_count),
+                       (uint32_t)rows, 0);
+    TASER_HIP_TRY(hipGetLastError());
+    TASER_HIP_TRY(hipStreamSynchronize(stream));
+    if (overlap) *overlap = both;
+    if (replaced) *replaced = replace ? 1 : 0;
+    return TASER_OK;
 }
 
 extern "C" int taser_cache_tune(taser_cache* c, int32_t stage_blocks, int32_t refresh_before_gather) {

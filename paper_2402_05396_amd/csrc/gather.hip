@@ -41,6 +41,7 @@ const uint8_t* taser_gather::zero_chunk() {
 
 int taser_launch_gather(const void* table, int64_t rows, int32_t row_bytes, int64_t pitch_bytes, const int32_t* ids,
                         int64_t n, void* out, hipStream_t stream) {
+    taser_clear_stale_hip_error();
     const int align = taser_gather::common_alignment((uint64_t)row_bytes | (uint64_t)pitch_bytes |
                                                      (uint64_t)(uintptr_t)table);
     const TableSource source{static_cast<const uint8_t*>(table), pitch_bytes, ids, rows};

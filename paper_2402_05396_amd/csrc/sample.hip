@@ -251,6 +251,7 @@ extern "C" int taser_sample_temporal(const taser_tcsr* g, const int32_t* roots, 
         if (n * k >= ((int64_t)1 << 31)) return taser_fail(TASER_E_RANGE, "sample_temporal: num_roots * k^hops must stay below 2^31");
         n *= k;
     }
+    taser_clear_stale_hip_error();
     hipStream_t stream = (hipStream_t)hip_stream;
     const int32_t* cur_roots = roots;
     const int64_t* cur_times = times;

@@ -11,6 +11,11 @@
 int taser_fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 int taser_fail_hip(hipError_t e, const char* what);
 
+// hipGetLastError() reports the last error of ANY earlier HIP call of this
+// thread, including other libraries' probes that were expected to fail. Entry
+// points that check their kernel launches with it call this first.
+inline void taser_clear_stale_hip_error() { (void)hipGetLastError(); }
+
 #define TASER_HIP_TRY(expr)                                    \
     do {                                                       \
         hipError_t taser_e_ = (expr);                          \

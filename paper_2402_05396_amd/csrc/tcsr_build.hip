@@ -16,6 +16,7 @@
 #include <new>
 #include <vector>
 
+#include "scan_kernels.h"
 #include "taser_internal.h"
 
 namespace {
@@ -127,74 +128,6 @@ __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const TaserRec* __
     hist[(size_t)threadIdx.x * num_blocks + blockIdx.x] = bins[threadIdx.x];
 }
 
-// ---- exclusive scan of a uint32 array (total < 2^31), three kernels --------
-constexpr int kScanItems = 16;
-constexpr int kScanChunk = kThreads * kScanItems;
-
-// Exclusive scan of one value per thread across the block; returns the prefix
-// and leaves the block total in *total (valid for all threads).
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t* total) {
-    __shared__ uint32_t wave_sum[kWaves];
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    uint32_t inc = x;
-    for (int d = 1; d < kWave; d <<= 1) {
-        const uint32_t y = __shfl_up(inc, d, kWave);
-        if (lane >= d) inc += y;
-    }
-    __syncthreads();                      // wave_sum may still be read from a previous call
-    if (lane == kWave - 1) wave_sum[wave] = inc;
-    __syncthreads();
-    uint32_t before = 0, all = 0;
-    for (int w = 0; w < kWaves; ++w) {
-        const uint32_t s = wave_sum[w];
-        if (w < wave) before += s;
-        all += s;
-    }
-    *total = all;
-    return before + inc - x;
-}
-
-__global__ __launch_bounds__(kThreads) void scan_reduce_kernel(const uint32_t* __restrict__ a, int64_t n,
-                                                               uint32_t* __restrict__ partial) {
-    const int64_t base = (int64_t)blockIdx.x * kScanChunk + (int64_t)threadIdx.x * kScanItems;
-    uint32_t s = 0;
-    for (int j = 0; j < kScanItems; ++j)
-        if (base + j < n) s += a[base + j];
-    uint32_t total;
-    block_exclusive_scan(s, &total);
-    if (threadIdx.x == 0) partial[blockIdx.x] = total;
-}
-
-// One block: partial[] becomes its own exclusive scan.
-__global__ __launch_bounds__(kThreads) void scan_partials_kernel(uint32_t* partial, int64_t count) {
-    uint32_t carry = 0;
-    for (int64_t base = 0; base < count; base += kThreads) {
-        const int64_t i = base + threadIdx.x;
-        const uint32_t x = i < count ? partial[i] : 0;
-        uint32_t total;
-        const uint32_t ex = block_exclusive_scan(x, &total);
-        if (i < count) partial[i] = carry + ex;
-        carry += total;
-    }
-}
-
-__global__ __launch_bounds__(kThreads) void scan_apply_kernel(uint32_t* __restrict__ a, int64_t n,
-                                                              const uint32_t* __restrict__ partial) {
-    const int64_t base = (int64_t)blockIdx.x * kScanChunk + (int64_t)threadIdx.x * kScanItems;
-    uint32_t v[kScanItems];
-    uint32_t s = 0;
-    for (int j = 0; j < kScanItems; ++j) {
-        v[j] = base + j < n ? a[base + j] : 0;
-        s += v[j];
-    }
-    uint32_t total;
-    uint32_t run = partial[blockIdx.x] + block_exclusive_scan(s, &total);
-    for (int j = 0; j < kScanItems; ++j) {
-        if (base + j < n) a[base + j] = run;
-        run += v[j];
-    }
-}
-
 // Stable scatter of one tile. offs = the scanned histogram: offs[bin*num_blocks
 // + block] is where this block's first item with digit `bin` goes.
 __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
@@ -295,6 +228,7 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
     if (num_nodes < 1 || num_nodes == 0x7fffffff) return taser_fail(TASER_E_RANGE, "tcsr_build: num_nodes = %d outside [1, 2^31 - 1)", num_nodes);
     if (num_entries > 0 && (!src || !dst || !ts)) return taser_fail(TASER_E_ARG, "tcsr_build: null src/dst/ts");
     if (flags & ~(uint32_t)TASER_INPUT_ON_DEVICE) return taser_fail(TASER_E_ARG, "tcsr_build: unknown flags 0x%x", flags);
+    taser_clear_stale_hip_error();
     hipStream_t stream = (hipStream_t)hip_stream;
     const int64_t n = num_entries;
 
@@ -355,7 +289,7 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
     TASER_HIP_TRY(indptr.alloc(((size_t)num_nodes + 1) * sizeof(int64_t)));
     const uint32_t num_blocks = blocks_for(n, kTile);
     const int64_t hist_len = (int64_t)kBins * num_blocks;
-    const unsigned scan_blocks = blocks_for(hist_len, kScanChunk);
+    const unsigned scan_blocks = taser_scan::num_partials(hist_len);
     if (n > 0) {
         {
             TaserProfileSpan span(stream, "tcsr_pack");
@@ -375,19 +309,8 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
                                    rec_a.as<TaserRec>(), key_a.as<int32_t>(), n, d, hist.as<uint32_t>(), num_blocks);
             }
             {
-                TaserProfileSpan span(stream, "tcsr_scan_reduce");
-                hipLaunchKernelGGL(scan_reduce_kernel, dim3(scan_blocks), dim3(kThreads), 0, stream,
-                                   hist.as<uint32_t>(), hist_len, partial.as<uint32_t>());
-            }
-            {
-                TaserProfileSpan span(stream, "tcsr_scan_partials");
-                hipLaunchKernelGGL(scan_partials_kernel, dim3(1), dim3(kThreads), 0, stream, partial.as<uint32_t>(),
-                                   (int64_t)scan_blocks);
-            }
-            {
-                TaserProfileSpan span(stream, "tcsr_scan_apply");
-                hipLaunchKernelGGL(scan_apply_kernel, dim3(scan_blocks), dim3(kThreads), 0, stream,
-                                   hist.as<uint32_t>(), hist_len, partial.as<uint32_t>());
+                TaserProfileSpan span(stream, "tcsr_scan");
+                taser_scan::exclusive_scan_u32(hist.as<uint32_t>(), hist_len, partial.as<uint32_t>(), stream);
             }
             {
                 TaserProfileSpan span(stream, "tcsr_radix_scatter");
@@ -427,6 +350,7 @@ extern "C" int taser_tcsr_size(const taser_tcsr* g, int64_t* num_entries, int32_
 extern "C" int taser_tcsr_view(const taser_tcsr* g, int64_t* indptr, int32_t* nbr, int64_t* ts, int32_t* eid,
                                void* hip_stream) {
     if (!g) return taser_fail(TASER_E_ARG, "tcsr_view: null graph");
+    taser_clear_stale_hip_error();
     hipStream_t stream = (hipStream_t)hip_stream;
     if (indptr)
         TASER_HIP_TRY(hipMemcpyAsync(indptr, g->indptr, ((size_t)g->num_nodes + 1) * sizeof(int64_t),

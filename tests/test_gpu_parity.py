@@ -356,3 +356,77 @@ def test_cache_prefetch_then_gather_on_two_streams():
     with pytest.raises(T.TaserError) as e:
         T.cache_gather(c, ids[:10])
     assert e.value.code == -1
+
+
+# ----------------------------------------------------------------------------- cache maintenance (Alg. 3)
+def test_cache_access_counts_and_epoch_end_match_the_oracle():
+    """Counters, top-k with ties, overlap threshold, replacement and what is served afterwards,
+    over several epochs of a drifting skewed request stream."""
+    rng = np.random.default_rng(31)
+    rows, dim, cap = 5000, 24, 700
+    host_np = rng.standard_normal((rows, dim)).astype(np.float32)
+    host = torch.from_numpy(host_np).pin_memory()
+    c = T.cache_init(host, cap, None, seed=2, staging_rows=512)
+    with pytest.raises(T.TaserError):
+        T.cache_epoch_end(c, 1)                                    # counting not enabled yet
+    T.cache_count_accesses(c)
+    resident = oracle.cache_random_residents(rows, cap, 2)
+    Q = np.zeros(rows, np.uint32)
+    p = 1.0 / np.arange(1, rows + 1) ** 1.1
+    p /= p.sum()
+    perm = rng.permutation(rows)
+    replaced_any = kept_any = False
+    for epoch in range(6):
+        if epoch % 2 == 0:
+            perm = np.roll(perm, 37 * epoch)                       # the hot set drifts
+        for batch in range(3):
+            n = (70000, 333, 20001)[batch]
+            ids = perm[rng.choice(rows, n, p=p)].astype(np.int32)
+            ids[::53] = -1
+            ids[5::97] = rows + 3                                  # out of range: served as zero rows, not counted
+            hm = torch.zeros(2, dtype=torch.int64, device="cuda")
+            out = T.cache_lookup(c, dev(ids), hit_miss=hm)
+            torch.cuda.synchronize()
+            ok = np.where(ids < rows, ids, -1)
+            assert out.cpu().numpy().tobytes() == oracle.gather(host_np, ok).tobytes()
+            assert tuple(hm.tolist()) == oracle.cache_hits(resident, rows, ok)
+            oracle.cache_count(ids, rows, Q)
+        assert np.array_equal(T.cache_access_counts(c).cpu().numpy().view(np.uint32), Q)
+        thr = (cap, 0, cap // 2, cap, cap - 5, 1)[epoch]
+        want_rep, want_ov, resident = oracle.cache_epoch_end(Q, resident, thr)
+        rep, ov = T.cache_epoch_end(c, thr)
+        assert (rep, ov) == (want_rep, want_ov)
+        assert np.array_equal(T.cache_residents(c).numpy(), resident)
+        assert not T.cache_access_counts(c).any()
+        replaced_any |= rep
+        kept_any |= not rep
+    assert replaced_any and kept_any
+
+
+def test_cache_epoch_end_ties_and_extremes():
+    """Nothing requested (all ties at zero: the smallest ids win), everything requested equally,
+    one row requested 2^20 times by a single batch, capacity 0 and capacity = rows."""
+    rows, dim = 1000, 4
+    host_np = np.arange(rows * dim, dtype=np.float32).reshape(rows, dim)
+    host = torch.from_numpy(host_np).pin_memory()
+    for cap in (0, 1, 37, rows):
+        c = T.cache_init(host, cap, None, seed=7)
+        T.cache_count_accesses(c)
+        resident = oracle.cache_random_residents(rows, cap, 7)
+        Q = np.zeros(rows, np.uint32)
+        streams = [np.zeros(0, np.int32), np.arange(rows, dtype=np.int32).repeat(3),
+                   np.concatenate([np.full(1 << 20, 999, np.int32), np.arange(0, rows, 7, dtype=np.int32)])]
+        for ids in streams:
+            if ids.shape[0]:
+                T.cache_lookup(c, dev(ids))
+                oracle.cache_count(ids, rows, Q)
+            assert np.array_equal(T.cache_access_counts(c).cpu().numpy().view(np.uint32), Q)
+            want_rep, want_ov, resident = oracle.cache_epoch_end(Q, resident, cap)
+            assert T.cache_epoch_end(c, cap) == (want_rep, want_ov)
+            assert np.array_equal(T.cache_residents(c).numpy(), resident)
+            probe = np.arange(rows, dtype=np.int32)
+            hm = torch.zeros(2, dtype=torch.int64, device="cuda")
+            out = T.cache_lookup(c, dev(probe), hit_miss=hm)
+            assert out.cpu().numpy().tobytes() == host_np.tobytes()
+            assert tuple(hm.tolist()) == (cap, rows - cap)
+            oracle.cache_count(probe, rows, Q)
