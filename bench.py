@@ -215,6 +215,31 @@ def main():
                             "kernel are mostly served by L2, so achieved can exceed what HBM alone could carry; "
                             "output_write_GBps is the dense output alone",
                     "output_write_GBps": round(out_bytes[dominant] / (per_kernel[dominant]["avg_ms"] * 1e-3) / 1e9, 1)}
+        if roofline["traffic"]:
+            t_gbps = roofline["traffic"] / (per_kernel[dominant]["avg_ms"] * 1e-3) / 1e9
+            roofline["traffic_GBps"] = round(t_gbps, 1)               # measured HBM-side bytes / measured time
+            roofline["traffic_frac"] = round(t_gbps / HBM_PEAK_GBPS, 4)
+
+    # ------------------------------------------------------------------ cache maintenance (outside the timed region)
+    # Cost of the access counters of Alg. 3 inside the classify kernel, and of one epoch-end
+    # top-k + overlap test (no replacement: the residents already are the hottest rows).
+    maintenance = None
+    if cache is not None:
+        T.cache_count_accesses(caches[0])
+        torch.cuda.synchronize()
+        T.profile_begin()
+        for i in range(10):
+            T.cache_prefetch(caches[0], batches[i % len(batches)]["ids"], stream=main)
+        torch.cuda.synchronize()
+        counted = T.profile_end()
+        t0 = time.perf_counter()
+        replaced, overlap = T.cache_epoch_end(caches[0], min_overlap=0)
+        t_epoch = time.perf_counter() - t0
+        T.cache_count_accesses(caches[0], False)
+        maintenance = {"classify_with_counting_ms": round(counted["cache_classify"][1] / counted["cache_classify"][0], 4),
+                       "classify_without_counting_ms": round(per_kernel["cache_classify"]["avg_ms"], 4),
+                       "epoch_end_wall_ms": round(t_epoch * 1e3, 3), "epoch_end_overlap": overlap,
+                       "rows": w.num_nodes, "capacity": cache.capacity}
 
     # A plain streaming kernel of known size (out[i] = in[i] + 1 over int32: 1 GiB read +
     # 1 GiB written): under rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings calibrate
@@ -278,7 +303,7 @@ def main():
                        "kernel_ms": round(build_dev_ms, 3),
                        "kernels": {n: round(ms, 3) for n, (_, ms) in build_kernels.items()}},
         "kernels": {n: {"launches": v["launches"], "avg_ms": round(v["avg_ms"], 4)} for n, v in per_kernel.items()},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "cache_maintenance": maintenance, "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(result), flush=True)
 
