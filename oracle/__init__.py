@@ -184,3 +184,24 @@ def cache_epoch_end(Q, resident, min_overlap):
                                          ctypes.c_int64(resident.shape[0]), ctypes.c_int64(min_overlap),
                                          _p(new), ctypes.byref(overlap))
     return bool(rep), int(overlap.value), new
+
+
+def candidate_encodings(nbr, count, want_identity=True):
+    """nbr int32[R, m], count int32[R] -> (freq int32[R, m], identity uint8[R, m, m] or None)."""
+    nbr, count = _c(nbr, np.int32), _c(count, np.int32)
+    R, m = nbr.shape
+    freq = np.empty((R, m), np.int32)
+    ident = np.empty((R, m, m), np.uint8) if want_identity else None
+    _load().oracle_candidate_encodings(_p(nbr), _p(count), ctypes.c_int64(R), ctypes.c_int32(m), _p(freq), _p(ident))
+    return freq, ident
+
+
+def select_weighted(weight, count, k, seed, hop):
+    """weight uint32[R, m], count int32[R] -> (sel int32[R, k], out_count int32[R])."""
+    weight, count = _c(weight, np.uint32), _c(count, np.int32)
+    R, m = weight.shape
+    sel = np.empty((R, k), np.int32)
+    out_count = np.empty(R, np.int32)
+    _load().oracle_select_weighted(_p(weight), _p(count), ctypes.c_int64(R), ctypes.c_int32(m), ctypes.c_int32(k),
+                                   ctypes.c_uint64(seed), ctypes.c_uint32(hop), _p(sel), _p(out_count))
+    return sel, out_count

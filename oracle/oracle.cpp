@@ -383,4 +383,71 @@ int oracle_cache_epoch_end(uint32_t* Q, int64_t rows, const int32_t* resident, i
     return replace;
 }
 
+/* Candidate-window encodings of the adaptive sampler's neighbor encoder
+ * (paper Sec. 3.2). For root i with candidates u_0..u_{c-1} (c = count[i] <= m,
+ * most recent first):
+ *   freq[i][j]        = number of candidates l < c with u_l == u_j  (the integer
+ *                       freq(u) that the frequency encoding takes as input);
+ *   identity[i][j][l] = 1 if u_j == u_l else 0, for j, l < c       (the identity
+ *                       encoding IE_(u_j, l)).
+ * Entries that involve a padding slot (j >= c or l >= c) are 0.
+ * identity may be null. */
+void oracle_candidate_encodings(const int32_t* nbr, const int32_t* count, int64_t num_roots, int32_t m,
+                                int32_t* freq, uint8_t* identity) {
+    for (int64_t i = 0; i < num_roots; ++i) {
+        const int32_t* u = nbr + i * m;
+        const int32_t c = count[i];
+        for (int32_t j = 0; j < m; ++j) {
+            int32_t f = 0;
+            for (int32_t l = 0; l < m; ++l) {
+                const int same = (j < c && l < c && u[j] == u[l]) ? 1 : 0;
+                f += same;
+                if (identity) identity[(i * m + j) * m + l] = (uint8_t)same;
+            }
+            freq[i * m + j] = f;
+        }
+    }
+}
+
+/* The second sampling line of Alg. 1 with a probability per (root, candidate):
+ * root i has c = count[i] candidates (slots 0..c-1 of its row of `m`) with integer
+ * weights weight[i][0..c-1] >= 1 (the quantised q(j|i)). If c <= k all candidates
+ * are kept in order; otherwise k successive draws without replacement, each
+ * proportional to the remaining weights, exactly as policy 2 of oracle_sample_hop:
+ * x = floor(draw(seed, hop, i, j) * W / 2^64), first remaining candidate whose
+ * running weight sum exceeds x. sel[i][j] = chosen candidate slot (or -1),
+ * out_count[i] = number chosen. */
+void oracle_select_weighted(const uint32_t* weight, const int32_t* count, int64_t num_roots, int32_t m,
+                            int32_t k, uint64_t seed, uint32_t hop, int32_t* sel, int32_t* out_count) {
+    for (int64_t i = 0; i < num_roots; ++i) {
+        int32_t* s = sel + i * k;
+        for (int32_t j = 0; j < k; ++j) s[j] = -1;
+        const int32_t c = count[i] < m ? count[i] : m;
+        if (c <= k) {
+            for (int32_t j = 0; j < c; ++j) s[j] = j;
+            out_count[i] = c < 0 ? 0 : c;
+            continue;
+        }
+        std::vector<uint64_t> w((size_t)c);
+        for (int32_t j = 0; j < c; ++j) w[(size_t)j] = weight[i * m + j];
+        for (int32_t j = 0; j < k; ++j) {
+            uint64_t W = 0;
+            for (int32_t l = 0; l < c; ++l) W += w[(size_t)l];
+            const uint64_t x = mulhi64(draw64(seed, hop, (uint64_t)i, (uint32_t)j), W);
+            uint64_t running = 0;
+            int32_t chosen = -1;
+            for (int32_t l = 0; l < c; ++l) {
+                running += w[(size_t)l];
+                if (running > x) {
+                    chosen = l;
+                    break;
+                }
+            }
+            w[(size_t)chosen] = 0;
+            s[j] = chosen;
+        }
+        out_count[i] = k;
+    }
+}
+
 }  // extern "C"

@@ -497,3 +497,73 @@ def test_cache_policy_converges_on_a_stationary_stream():
         assert hit_rate[1] > hit_rate[0] + 0.2
         rates.append(hit_rate[-1])
     assert rates[0] < rates[1] < rates[2]
+
+
+# --------------------------------------------------------------------------- candidate-window products (Sec. 3.2)
+def test_candidate_encodings_equal_numpy():
+    """freq(u) = how often u appears among the valid candidates; IE = pairwise equality."""
+    rng = np.random.default_rng(10)
+    R, m = 200, 25
+    nbr = rng.integers(0, 6, (R, m)).astype(np.int32)               # few distinct ids: many repeats
+    count = rng.integers(0, m + 1, R).astype(np.int32)
+    count[:3] = (0, 1, m)
+    for i in range(R):
+        nbr[i, count[i]:] = -1                                      # padding never matches anything
+    freq, ident = oracle.candidate_encodings(nbr, count)
+    valid = np.arange(m)[None, :] < count[:, None]
+    eq = (nbr[:, :, None] == nbr[:, None, :]) & valid[:, :, None] & valid[:, None, :]
+    assert np.array_equal(ident, eq.astype(np.uint8))
+    assert np.array_equal(freq, eq.sum(axis=2).astype(np.int32))
+    for i in (3, 50, 199):                                          # and through numpy.unique, independently
+        ids, cnt = np.unique(nbr[i, :count[i]], return_counts=True)
+        lut = dict(zip(ids.tolist(), cnt.tolist()))
+        assert freq[i, :count[i]].tolist() == [lut[u] for u in nbr[i, :count[i]].tolist()]
+        assert not freq[i, count[i]:].any()
+    f2, none = oracle.candidate_encodings(nbr, count, want_identity=False)
+    assert none is None and np.array_equal(f2, freq)
+
+
+def test_select_weighted_replay_and_closed_form():
+    """Per-slot weights: step-by-step replay in Python integers, the closed form of successive
+    sampling (chi-square over ordered pairs), agreement with the per-edge-weight policy when the
+    per-slot weights are those edge weights, and the keep-everything case."""
+    rng = np.random.default_rng(12)
+    R, m, k = 300, 9, 4
+    weight = rng.integers(1, 1 << 16, (R, m)).astype(np.uint32)
+    count = rng.integers(0, m + 1, R).astype(np.int32)
+    sel, oc = oracle.select_weighted(weight, count, k, seed=5, hop=1)
+    for i in range(R):
+        c = int(count[i])
+        if c <= k:
+            assert sel[i].tolist() == list(range(c)) + [-1] * (k - c) and oc[i] == c
+            continue
+        rem = [int(x) for x in weight[i, :c]]
+        for j in range(k):
+            x = (oracle.draw64(5, 1, i, j) * sum(rem)) >> 64
+            acc = 0
+            for l, wl in enumerate(rem):
+                acc += wl
+                if acc > x:
+                    break
+            rem[l] = 0
+            assert sel[i, j] == l
+        assert oc[i] == k
+    w = np.array([1, 2, 3, 4, 10], np.uint32)
+    n = 120000
+    sel, _ = oracle.select_weighted(np.tile(w, (n, 1)), np.full(n, 5, np.int32), 2, seed=77, hop=0)
+    probs = _successive_probs([int(x) for x in w], 2)
+    obs = np.array([np.sum((sel[:, 0] == a) & (sel[:, 1] == b)) for (a, b) in probs])
+    exp = np.array(list(probs.values())) * n
+    assert obs.sum() == n and (((obs - exp) ** 2) / exp).sum() < stats.chi2.ppf(1 - 1e-4, len(exp) - 1)
+    # same draws as the per-edge-weight policy of the finder when the weights coincide
+    src, dst, ts, eid = _random_events(rng, 15, 3000, 4000, True)
+    g = oracle.tcsr_build(src, dst, ts, eid, 15)
+    ew = rng.integers(1, 1 << 16, 3000).astype(np.uint32)
+    roots = rng.integers(0, 15, 100).astype(np.int32)
+    times = rng.integers(0, 4000, 100).astype(np.int64)
+    cand = oracle.sample_hop(g, roots, times, 9, oracle.RECENT, 3, 0)
+    kept = oracle.sample_hop(g, roots, times, 4, oracle.WEIGHTED, 3, 0, m=9, edge_weight=ew)
+    sel, oc = oracle.select_weighted(ew[np.maximum(cand["eid"], 0)], cand["count"], 4, seed=3, hop=0)
+    assert np.array_equal(oc, kept["count"])
+    picked = np.where(sel >= 0, np.take_along_axis(cand["eid"], np.maximum(sel, 0), axis=1), -1)
+    assert np.array_equal(picked, kept["eid"])
