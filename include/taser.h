@@ -142,6 +142,48 @@ int taser_sample_temporal(const taser_tcsr* g, const int32_t* roots, const int64
                           const taser_hop_out* out, void* hip_stream);
 
 /* ---------------------------------------------------------------------------
+ * Candidate-window products of the adaptive sampler (Sec. 3 overview, Alg. 1:
+ * a static finder returns m candidates per root, a network scores them, n of
+ * the m are kept; Sec. 3.2: the network's frequency encoding takes the integer
+ * freq(u_j), the identity encoding is the matrix IE[j][l] = 1 if u_j = u_l).
+ * The candidates are the output of a taser_sample_temporal hop with k = m
+ * (their feature rows: taser_gather_features on its eid array).
+ *
+ * taser_candidate_encodings, for root i with c = clamp(count[i], 0, m)
+ * candidates nbr[i][0..c):
+ *   freq[i][j]        = number of l < c with nbr[i][l] == nbr[i][j], for j < c
+ *   identity[i][j][l] = 1 if j < c, l < c and nbr[i][j] == nbr[i][l], else 0
+ * and 0 wherever a padding slot (index >= c) is involved.
+ *   nbr int32[num_roots*m], count int32[num_roots]                   device
+ *   freq int32[num_roots*m], identity uint8[num_roots*m*m] or NULL   device
+ *   m in [1, TASER_MAX_M], num_roots * m < 2^31
+ *
+ * taser_select_weighted is the second draw of Alg. 1 with one weight per
+ * (root, candidate): weight[i][j] >= 1 is the quantised q(j|i) of candidate j.
+ * With c as above: c <= k keeps all candidates, sel[i][j] = j for j < c.
+ * Otherwise k successive draws without replacement, each proportional to the
+ * remaining weights, exactly as TASER_WEIGHTED: x = floor(draw * W / 2^64)
+ * with the Philox draw keyed (seed, hop, i, j); sel[i][j] = first remaining
+ * candidate whose running weight sum exceeds x. Unused slots of sel are -1;
+ * out_count[i] = min(c, k).
+ *   weight uint32[num_roots*m], count int32[num_roots]               device
+ *   sel int32[num_roots*k], out_count int32[num_roots]               device
+ *   candidates, kept: both NULL, or host pointers to structs of device
+ *     buffers (count members unused): kept->nbr/eid/ts [num_roots*k] receive
+ *     candidates->nbr/eid/ts [num_roots*m] at the selected slots (padding where
+ *     sel is -1), ready to be the next hop's roots and times.
+ *   k in [1, TASER_MAX_K], m in [1, TASER_MAX_M], num_roots * max(m,k) < 2^31
+ * With weight[i][j] = edge_weight[eid of candidate j] the result equals policy
+ * TASER_WEIGHTED of taser_sample_temporal for the same seed, hop and roots.
+ * ------------------------------------------------------------------------- */
+int taser_candidate_encodings(const int32_t* nbr, const int32_t* count, int64_t num_roots, int32_t m,
+                              int32_t* freq, uint8_t* identity, void* hip_stream);
+
+int taser_select_weighted(const uint32_t* weight, const int32_t* count, int64_t num_roots, int32_t m,
+                          int32_t k, uint64_t seed, uint32_t hop, int32_t* sel, int32_t* out_count,
+                          const taser_hop_out* candidates, const taser_hop_out* kept, void* hip_stream);
+
+/* ---------------------------------------------------------------------------
  * Feature slicing from a table in device memory (Sec. 3.4; Alg. 3 "serve
  * x_e"): out row i = the row_bytes bytes of table row ids[i]; ids[i] < 0 gives
  * a zero row. The output is dense (row i at byte offset i * row_bytes).

@@ -19,7 +19,7 @@ INPUT_ON_DEVICE = 1
 MAX_K, MAX_M, MAX_HOPS = 64, 64, 3
 
 EXPORTS = ("taser_tcsr_build", "taser_tcsr_size", "taser_tcsr_view", "taser_tcsr_free", "taser_sample_temporal",
-           "taser_gather_features", "taser_cache_init", "taser_cache_lookup", "taser_cache_prefetch", "taser_cache_gather", "taser_cache_tune", "taser_cache_count_accesses", "taser_cache_access_counts",
+           "taser_candidate_encodings", "taser_select_weighted", "taser_gather_features", "taser_cache_init", "taser_cache_lookup", "taser_cache_prefetch", "taser_cache_gather", "taser_cache_tune", "taser_cache_count_accesses", "taser_cache_access_counts",
            "taser_cache_epoch_end", "taser_cache_residents",
            "taser_cache_free", "taser_profile_begin", "taser_profile_end", "taser_last_error")
 
@@ -57,6 +57,9 @@ def lib():
         L.taser_tcsr_free.argtypes = [vp]
         L.taser_tcsr_free.restype = None
         L.taser_sample_temporal.argtypes = [vp, vp, vp, i64, i32, i32, i32, u64, i32, vp,
+                                            ctypes.POINTER(_HopOut), vp]
+        L.taser_candidate_encodings.argtypes = [vp, vp, i64, i32, vp, vp, vp]
+        L.taser_select_weighted.argtypes = [vp, vp, i64, i32, i32, u64, u32, vp, vp, ctypes.POINTER(_HopOut),
                                             ctypes.POINTER(_HopOut), vp]
         L.taser_gather_features.argtypes = [vp, i64, i32, i64, vp, i64, vp, vp]
         L.taser_cache_init.argtypes = [vp, i64, i32, i64, i64, vp, u64, i64, vp, ctypes.POINTER(vp)]
@@ -189,6 +192,52 @@ def sample_temporal(g, roots, times, k, hops, policy, seed, m=0, edge_weight=Non
     _check(lib().taser_sample_temporal(g.handle, _ptr(roots), _ptr(times), n, k, hops, policy, seed, m,
                                        _ptr(edge_weight), arr, _stream(stream)))
     return out
+
+
+def candidate_encodings(nbr, count, want_identity=True, stream=None):
+    """taser_candidate_encodings. nbr int32[R, m], count int32[R] ->
+    (freq int32[R, m], identity uint8[R, m, m] or None)."""
+    _want(nbr, torch.int32, "nbr")
+    _want(count, torch.int32, "count")
+    if nbr.dim() != 2 or count.numel() != nbr.shape[0]:
+        raise ValueError("nbr must be [R, m] and count [R]")
+    R, m = nbr.shape
+    freq = torch.empty((R, m), dtype=torch.int32, device=nbr.device)
+    ident = torch.empty((R, m, m), dtype=torch.uint8, device=nbr.device) if want_identity else None
+    _check(lib().taser_candidate_encodings(_ptr(nbr), _ptr(count), R, m, _ptr(freq), _ptr(ident), _stream(stream)))
+    return freq, ident
+
+
+def select_weighted(weight, count, k, seed, hop, candidates=None, stream=None):
+    """taser_select_weighted. weight int32[R, m] (uint32 bits), count int32[R] ->
+    (sel int32[R, k], out_count int32[R], kept). With `candidates` (a dict of
+    nbr/eid/ts [R, m] as sample_temporal returns) kept is a dict of nbr/eid/ts
+    [R, k] and count, else None."""
+    _want(weight, torch.int32, "weight (uint32 bits in an int32 tensor)")
+    _want(count, torch.int32, "count")
+    if weight.dim() != 2 or count.numel() != weight.shape[0]:
+        raise ValueError("weight must be [R, m] and count [R]")
+    R, m = weight.shape
+    d = weight.device
+    sel = torch.empty((R, k), dtype=torch.int32, device=d)
+    out_count = torch.empty((R,), dtype=torch.int32, device=d)
+    cand_arg = kept_arg = kept = None
+    if candidates is not None:
+        for name, dt in (("nbr", torch.int32), ("eid", torch.int32), ("ts", torch.int64)):
+            _want(candidates[name], dt, f"candidates.{name}")
+            if candidates[name].numel() != R * m:
+                raise ValueError(f"candidates.{name} must hold R*m elements")
+        kept = dict(nbr=torch.empty((R, k), dtype=torch.int32, device=d),
+                    eid=torch.empty((R, k), dtype=torch.int32, device=d),
+                    ts=torch.empty((R, k), dtype=torch.int64, device=d), count=out_count)
+        cand_arg, kept_arg = _HopOut(), _HopOut()
+        for name in ("nbr", "eid", "ts"):
+            setattr(cand_arg, name, candidates[name].data_ptr())
+            setattr(kept_arg, name, kept[name].data_ptr())
+        cand_arg, kept_arg = ctypes.byref(cand_arg), ctypes.byref(kept_arg)
+    _check(lib().taser_select_weighted(_ptr(weight), _ptr(count), R, m, k, seed, hop, _ptr(sel), _ptr(out_count),
+                                       cand_arg, kept_arg, _stream(stream)))
+    return sel, out_count, kept
 
 
 def gather_features(table, ids, out=None, row_elems=None, stream=None):

@@ -255,6 +255,105 @@ def test_sampler_is_deterministic_and_independent_of_batch_split():
     assert torch.equal(a[0]["count"], c[0]["count"])
 
 
+# ----------------------------------------------------------------------------- candidate-window products
+@pytest.mark.parametrize("m", [1, 5, 16, 25, 32, 33, 64])
+def test_candidate_encodings_match_the_oracle(m):
+    """Frequency and identity encodings for every lane-group width, with repeated
+    neighbors, short windows, counts beyond m and below 0, and a ragged last wave."""
+    rng = np.random.default_rng(m)
+    for R in (0, 1, 3, 64, 1000 + m):
+        nbr = rng.integers(0, max(2, m // 3), (R, m)).astype(np.int32)          # few distinct nodes: many repeats
+        nbr[::7] = rng.integers(0, 1 << 30, (len(nbr[::7]), m))                  # mostly distinct rows
+        count = rng.integers(0, m + 1, R).astype(np.int32)
+        count[::5] = m
+        count[3::11] = m + 9
+        count[4::13] = -2
+        want_f, want_i = oracle.candidate_encodings(nbr, count)
+        got_f, got_i = T.candidate_encodings(dev(nbr), dev(count))
+        torch.cuda.synchronize()
+        assert np.array_equal(got_f.cpu().numpy(), want_f)
+        assert np.array_equal(got_i.cpu().numpy(), want_i)
+        got_f2, none = T.candidate_encodings(dev(nbr), dev(count), want_identity=False)
+        assert none is None and torch.equal(got_f, got_f2)
+
+
+def test_candidate_encodings_unaligned_identity_output():
+    """The identity bytes of a wave are written as aligned 4-byte words with byte
+    stores at the ragged ends: give the output every alignment, guard bytes around it."""
+    rng = np.random.default_rng(2)
+    R, m = 37, 7
+    nbr = rng.integers(0, 3, (R, m)).astype(np.int32)
+    count = rng.integers(0, m + 1, R).astype(np.int32)
+    _, want_i = oracle.candidate_encodings(nbr, count)
+    nbr_d, count_d = dev(nbr), dev(count)
+    freq = torch.empty((R, m), dtype=torch.int32, device="cuda")
+    for off in range(4):
+        buf = torch.full((R * m * m + 16,), 0xEE, dtype=torch.uint8, device="cuda")
+        view = buf[4 + off:4 + off + R * m * m]
+        T._check(T.lib().taser_candidate_encodings(T._ptr(nbr_d), T._ptr(count_d), R, m, T._ptr(freq), T._ptr(view),
+                                                   T._stream(None)))
+        torch.cuda.synchronize()
+        got = buf.cpu().numpy()
+        assert np.array_equal(got[4 + off:4 + off + R * m * m], want_i.ravel())
+        assert (got[:4 + off] == 0xEE).all() and (got[4 + off + R * m * m:] == 0xEE).all()
+
+
+@pytest.mark.parametrize("m,k", [(2, 1), (25, 10), (16, 16), (32, 10), (64, 32), (64, 64), (5, 10), (40, 3)])
+def test_select_weighted_matches_the_oracle(m, k):
+    rng = np.random.default_rng(1000 * m + k)
+    for R in (0, 1, 65, 2000 + k):
+        weight = rng.integers(1, 1 << 16, (R, m), dtype=np.uint64).astype(np.uint32)
+        weight[::3] = rng.integers(1, 1 << 32, (len(weight[::3]), m), dtype=np.uint64).astype(np.uint32)
+        weight[1::9] = 0xFFFFFFFF
+        count = rng.integers(0, m + 1, R).astype(np.int32)
+        count[::4] = m
+        count[5::17] = m + 3
+        for hop in (0, 2):
+            want_sel, want_cnt = oracle.select_weighted(weight, count, k, seed=77, hop=hop)
+            sel, cnt, kept = T.select_weighted(dev(weight.view(np.int32)), dev(count), k, 77, hop)
+            torch.cuda.synchronize()
+            assert kept is None
+            assert np.array_equal(sel.cpu().numpy(), want_sel)
+            assert np.array_equal(cnt.cpu().numpy(), want_cnt)
+
+
+def test_adaptive_two_hop_pipeline_on_the_flights_shaped_workload():
+    """Alg. 1 as the adaptive sampler runs it, per hop: m most recent candidates, their
+    encodings and feature rows, a weight per (root, candidate), n of m kept, kept
+    neighbors become the next hop's roots. The weights stand in for the network's
+    output: here the per-edge table, so the whole pipeline must also reproduce the
+    one-call weighted policy."""
+    w = W.make(4, num_batches=1)
+    g, g_ref = build_both(w.src, w.dst, w.ts, w.eid, w.num_nodes)
+    table = dev(w.edge_feat)
+    weight_dev = dev(w.edge_weight.view(np.int32))
+    roots, times = w.batches[0]
+    fused = oracle.sample_temporal(g_ref, roots, times, w.k, 2, W.WEIGHTED, 42, w.m, w.edge_weight, THREADS)
+    cur_roots, cur_times = dev(roots), dev(times)
+    ref_roots, ref_times = roots, times
+    for hop in range(2):
+        cand = T.sample_temporal(g, cur_roots, cur_times, w.m, 1, T.RECENT, seed=0)[0]
+        ref_cand = oracle.sample_temporal(g_ref, ref_roots, ref_times, w.m, 1, W.RECENT, 0, threads=THREADS)[0]
+        freq, ident = T.candidate_encodings(cand["nbr"], cand["count"])
+        ref_freq, ref_ident = oracle.candidate_encodings(ref_cand["nbr"], ref_cand["count"])
+        check_gather(w.edge_feat, table, cand["eid"], ref_cand["eid"])          # all m candidates' rows
+        slot_w = torch.where(cand["eid"] >= 0, weight_dev[cand["eid"].clamp(min=0).long()], 0).contiguous()
+        ref_slot_w = np.where(ref_cand["eid"] >= 0, w.edge_weight[np.maximum(ref_cand["eid"], 0)], 0).astype(np.uint32)
+        sel, cnt, kept = T.select_weighted(slot_w, cand["count"], w.k, 42, hop, candidates=cand)
+        ref_sel, ref_cnt = oracle.select_weighted(ref_slot_w, ref_cand["count"], w.k, 42, hop)
+        torch.cuda.synchronize()
+        assert np.array_equal(freq.cpu().numpy(), ref_freq) and np.array_equal(ident.cpu().numpy(), ref_ident)
+        assert np.array_equal(sel.cpu().numpy(), ref_sel) and np.array_equal(cnt.cpu().numpy(), ref_cnt)
+        take = np.maximum(ref_sel, 0)
+        for f, pad in (("nbr", -1), ("eid", -1), ("ts", 0)):
+            want = np.where(ref_sel >= 0, np.take_along_axis(ref_cand[f], take, axis=1), pad)
+            assert np.array_equal(kept[f].cpu().numpy(), want), (hop, f)
+            assert np.array_equal(want, fused[hop][f]), (hop, f)                # equals the one-call policy
+        assert np.array_equal(ref_cnt, fused[hop]["count"])
+        cur_roots, cur_times = kept["nbr"].reshape(-1), kept["ts"].reshape(-1)
+        ref_roots, ref_times = fused[hop]["nbr"].ravel(), fused[hop]["ts"].ravel()
+
+
 # ----------------------------------------------------------------------------- gather edge cases
 @pytest.mark.parametrize("dtype,dim,pad,offset", [
     (np.float32, 16, 0, 0),      # 64-byte rows, 16-byte vectors

@@ -64,6 +64,23 @@ def test_argument_errors_are_reported_without_a_gpu():
         setattr(big[0], f, 8)
     assert lib.taser_sample_temporal(g, one, one, 2 ** 28, 10, 1, 0, 0, 0, None, big, None) == E_RANGE
 
+    assert lib.taser_candidate_encodings(one, one, -1, 25, one, one, None) == E_ARG
+    assert lib.taser_candidate_encodings(one, one, 4, 0, one, one, None) == E_RANGE
+    assert lib.taser_candidate_encodings(one, one, 4, 65, one, one, None) == E_RANGE
+    assert lib.taser_candidate_encodings(one, one, 2 ** 27, 25, one, one, None) == E_RANGE
+    assert lib.taser_candidate_encodings(None, one, 4, 25, one, one, None) == E_ARG
+    assert lib.taser_candidate_encodings(one, one, 4, 25, None, one, None) == E_ARG
+    assert lib.taser_candidate_encodings(None, None, 0, 25, None, None, None) == 0      # nothing to do
+    assert lib.taser_select_weighted(one, one, -1, 25, 10, 0, 0, one, one, None, None, None) == E_ARG
+    assert lib.taser_select_weighted(one, one, 4, 0, 10, 0, 0, one, one, None, None, None) == E_RANGE
+    assert lib.taser_select_weighted(one, one, 4, 25, 65, 0, 0, one, one, None, None, None) == E_RANGE
+    assert lib.taser_select_weighted(one, one, 2 ** 27, 25, 10, 0, 0, one, one, None, None, None) == E_RANGE
+    assert lib.taser_select_weighted(None, one, 4, 25, 10, 0, 0, one, one, None, None, None) == E_ARG
+    assert lib.taser_select_weighted(one, one, 4, 25, 10, 0, 0, one, None, None, None, None) == E_ARG
+    assert lib.taser_select_weighted(one, one, 4, 25, 10, 0, 0, one, one, out, None, None) == E_ARG   # kept missing
+    assert lib.taser_select_weighted(one, one, 4, 25, 10, 0, 0, one, one, out, out, None) == E_ARG    # null buffers
+    assert lib.taser_select_weighted(None, None, 0, 25, 10, 0, 0, None, None, None, None, None) == 0
+
     assert lib.taser_gather_features(one, 4, 0, 16, one, 1, one, None) == E_ARG
     assert lib.taser_gather_features(one, 4, 15, 16, one, 1, one, None) == E_ARG
     assert lib.taser_gather_features(one, 4, 16, 8, one, 1, one, None) == E_ARG
