@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "oracle.cpp")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
-RECENT, UNIFORM, WEIGHTED = 0, 1, 2
+RECENT, UNIFORM, WEIGHTED, INVERSE_TIMESPAN = 0, 1, 2, 3
 
 
 def build(force=False):
@@ -205,3 +205,20 @@ def select_weighted(weight, count, k, seed, hop):
     _load().oracle_select_weighted(_p(weight), _p(count), ctypes.c_int64(R), ctypes.c_int32(m), ctypes.c_int32(k),
                                    ctypes.c_uint64(seed), ctypes.c_uint32(hop), _p(sel), _p(out_count))
     return sel, out_count
+
+
+def batch_draw(score, b, seed, iteration):
+    """score uint32[n] -> int32[b] edge indices drawn with probability score / sum(score)."""
+    score = _c(score, np.uint32)
+    out = np.empty(b, np.int32)
+    _load().oracle_batch_draw(_p(score), ctypes.c_int64(score.shape[0]), ctypes.c_int64(b), ctypes.c_uint64(seed),
+                              ctypes.c_uint64(iteration), _p(out))
+    return out
+
+
+def score_update(score, idx, value):
+    """In place: score[idx[j]] = value[j] for j in order (score is uint32[n])."""
+    assert score.dtype == np.uint32 and score.flags.c_contiguous
+    idx, value = _c(idx, np.int32), _c(value, np.uint32)
+    _load().oracle_score_update(_p(score), ctypes.c_int64(score.shape[0]), _p(idx), _p(value),
+                                ctypes.c_int64(idx.shape[0]))

@@ -17,7 +17,8 @@
  * Pins (tests/test_oracle_*.py): Philox known-answer vectors, numpy.lexsort,
  * numpy.searchsorted, pure-Python brute force from the raw event list,
  * explicit-array Fisher-Yates, closed-form successive-sampling probabilities
- * and chi-square tests, numpy.take. No function here is unpinned.
+ * and chi-square tests, numpy.take, numpy.cumsum + searchsorted, the real-valued
+ * 1/delta law, sequential Python replays. No function here is unpinned.
  *
  * Precision: all selection arithmetic is integer (the paper states none);
  * feature rows are copied as bytes.
@@ -170,6 +171,14 @@ int oracle_tcsr_build(const int32_t* src, const int32_t* dst, const int64_t* ts,
  *         without replacement, each proportional to the remaining weights:
  *         x = floor(draw * W / 2^64) with W the remaining total, pick the
  *         first remaining candidate whose running weight sum exceeds x.
+ *   policy 3 (inverse timespan, the heuristic sampler of TGAT that the paper's
+ *         introduction and related work describe: past neighbors are sampled
+ *         with probabilities inversely proportional to their time deltas):
+ *         over ALL cnt valid entries, entry p has the integer weight
+ *         w_p = max(1, floor(2^32 / (t - ts[p]))) (t - ts[p] >= 1 by the strict
+ *         cutoff). When cnt <= k all entries are returned in most-recent
+ *         order; otherwise k successive draws without replacement as in
+ *         policy 2, the running sum taken in list order (oldest entry first).
  * A root with roots[q] < 0 (padding from the previous hop) has no neighbors.
  * Unused slots hold nbr = -1, eid = -1, ts = 0; count[q] = slots filled.
  * Returns 0, -1 on a bad argument. */
@@ -179,7 +188,7 @@ int oracle_sample_hop(const int64_t* indptr, const int32_t* nbr, const int64_t* 
                       uint64_t seed, uint32_t hop, int32_t m, const uint32_t* edge_weight,
                       int32_t* out_nbr, int32_t* out_eid, int64_t* out_ts, int32_t* out_count,
                       int threads) {
-    if (k < 1 || policy < 0 || policy > 2) return -1;
+    if (k < 1 || policy < 0 || policy > 3) return -1;
     if (policy == 2 && (edge_weight == nullptr || m < 1)) return -1;
     int bad = 0;
 #ifdef _OPENMP
@@ -210,7 +219,7 @@ int oracle_sample_hop(const int64_t* indptr, const int32_t* nbr, const int64_t* 
             if (ts[p] < t) ++cnt;
 
         std::vector<int64_t> pick;  // positions inside the list, one per filled slot
-        if (policy == 0 || (policy == 1 && cnt <= k)) {
+        if (policy == 0 || ((policy == 1 || policy == 3) && cnt <= k)) {
             const int64_t c = std::min<int64_t>(k, cnt);
             for (int64_t j = 0; j < c; ++j) pick.push_back(cnt - 1 - j);
         } else if (policy == 1) {
@@ -224,6 +233,29 @@ int oracle_sample_hop(const int64_t* indptr, const int32_t* nbr, const int64_t* 
                 const int64_t r = j + (int64_t)mulhi64(u, (uint64_t)(cnt - j));
                 const int64_t chosen = a(r);
                 moved[r] = a(j);
+                pick.push_back(chosen);
+            }
+        } else if (policy == 3) {
+            std::vector<uint64_t> w((size_t)cnt);
+            for (int64_t p = 0; p < cnt; ++p) {
+                const uint64_t delta = (uint64_t)t - (uint64_t)ts[lo + p];   // exact: t > ts[lo + p]
+                const uint64_t inv = (uint64_t)(((unsigned __int128)1 << 32) / delta);
+                w[(size_t)p] = inv < 1 ? 1 : inv;
+            }
+            for (int32_t j = 0; j < k; ++j) {
+                uint64_t W = 0;
+                for (int64_t p = 0; p < cnt; ++p) W += w[(size_t)p];
+                const uint64_t x = mulhi64(draw64(seed, hop, (uint64_t)q, (uint32_t)j), W);
+                uint64_t running = 0;
+                int64_t chosen = -1;
+                for (int64_t p = 0; p < cnt; ++p) {
+                    running += w[(size_t)p];
+                    if (running > x) {
+                        chosen = p;
+                        break;
+                    }
+                }
+                w[(size_t)chosen] = 0;
                 pick.push_back(chosen);
             }
         } else {
@@ -447,6 +479,47 @@ void oracle_select_weighted(const uint32_t* weight, const int32_t* count, int64_
             s[j] = chosen;
         }
         out_count[i] = k;
+    }
+}
+
+/* Adaptive mini-batch selection (paper Sec. 3.1: a list of importance scores P
+ * over the training edges, initialised uniformly; a batch of training edges is
+ * sampled with probability proportional to the scores; after the forward pass
+ * the scores of the batch's edges are overwritten).
+ *
+ * Scores are integers (the quantised sigmoid(y) + gamma of Eq. (4) is produced
+ * outside this path). oracle_batch_draw makes b independent draws, draw j:
+ *   x = floor(draw(seed, tag 0x4253454C, root = iteration, slot = j) * W / 2^64)
+ * with W the sum of all scores, out[j] = the first edge whose running score sum
+ * exceeds x (so P(out[j] = e) = score[e] / W up to 2^-64 rounding). W == 0 gives -1. */
+void oracle_batch_draw(const uint32_t* score, int64_t n, int64_t b, uint64_t seed, uint64_t iteration,
+                       int32_t* out) {
+    std::vector<uint64_t> running((size_t)n);
+    uint64_t W = 0;
+    for (int64_t e = 0; e < n; ++e) {
+        W += score[e];
+        running[(size_t)e] = W;
+    }
+    for (int64_t j = 0; j < b; ++j) {
+        out[j] = -1;
+        if (W == 0) continue;
+        const uint64_t x = mulhi64(draw64(seed, 0x4253454Cu, iteration, (uint32_t)j), W);
+        for (int64_t e = 0; e < n; ++e) {
+            if (running[(size_t)e] > x) {
+                out[j] = (int32_t)e;
+                break;
+            }
+        }
+    }
+}
+
+/* Score update after an iteration: for j = 0..b-1 in order, score[idx[j]] =
+ * value[j] (an edge drawn twice keeps the later value); entries with idx
+ * outside [0, n) are skipped. */
+void oracle_score_update(uint32_t* score, int64_t n, const int32_t* idx, const uint32_t* value, int64_t b) {
+    for (int64_t j = 0; j < b; ++j) {
+        if (idx[j] < 0 || idx[j] >= n) continue;
+        score[idx[j]] = value[j];
     }
 }
 

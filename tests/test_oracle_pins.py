@@ -567,3 +567,169 @@ def test_select_weighted_replay_and_closed_form():
     assert np.array_equal(oc, kept["count"])
     picked = np.where(sel >= 0, np.take_along_axis(cand["eid"], np.maximum(sel, 0), axis=1), -1)
     assert np.array_equal(picked, kept["eid"])
+
+
+# --------------------------------------------------------------------------- inverse-timespan policy
+def _timed_node(ts_list, t_after=3):
+    """One node (id 0) whose entries have the given ascending timestamps (neighbor id =
+    position), plus a few later entries that a query must not see."""
+    ts = np.array(list(ts_list) + [max(ts_list) + 10 ** 9 + i for i in range(t_after)], np.int64)
+    n = ts.shape[0]
+    return oracle.tcsr_build(np.zeros(n, np.int32), np.arange(n, dtype=np.int32), ts,
+                             (500 + np.arange(n)).astype(np.int32), 1)
+
+
+def _inverse_weights(ts_list, t):
+    return [max(1, (1 << 32) // (t - x)) for x in ts_list]           # Python big integers
+
+
+def test_inverse_timespan_equals_stepwise_python():
+    """Replay with Python integers: weights floor(2^32 / delta), running sums in list order,
+    one draw per slot scaled to the remaining total."""
+    rng = np.random.default_rng(8)
+    ts_list = sorted(int(x) for x in rng.integers(0, 5000, 40))
+    g, t = _timed_node(ts_list), 5003
+    R, k = 300, 6
+    o = oracle.sample_hop(g, np.zeros(R, np.int32), np.full(R, t, np.int64), k, oracle.INVERSE_TIMESPAN, 21, 2)
+    w0 = _inverse_weights(ts_list, t)
+    for q in range(R):
+        rem = list(w0)
+        for j in range(k):
+            x = (oracle.draw64(21, 2, q, j) * sum(rem)) >> 64
+            acc, pick = 0, None
+            for p, wp in enumerate(rem):
+                acc += wp
+                if acc > x:
+                    pick = p
+                    break
+            rem[pick] = 0
+            assert o["nbr"][q, j] == pick and o["ts"][q, j] == ts_list[pick]
+        assert o["count"][q] == k and len(set(o["nbr"][q].tolist())) == k
+
+
+def test_inverse_timespan_probabilities_are_inverse_to_the_time_delta():
+    """Slot 0 is drawn with probability (1/delta_p) / sum(1/delta): chi-square against the
+    real-valued law the heuristic states (the integer weights deviate from it by < 2^-20
+    relative here); ordered pairs against the successive-sampling closed form."""
+    deltas = [1, 2, 3, 5, 8, 13, 100, 1000]
+    t = 10 ** 6
+    ts_list = sorted(t - d for d in deltas)                            # oldest first
+    g = _timed_node(ts_list)
+    R = 120000
+    o = oracle.sample_hop(g, np.zeros(R, np.int32), np.full(R, t, np.int64), 2, oracle.INVERSE_TIMESPAN, 5, 0,
+                          threads=4)
+    inv = np.array([1.0 / (t - x) for x in ts_list])
+    obs = np.bincount(o["nbr"][:, 0], minlength=len(deltas))
+    exp = inv / inv.sum() * R
+    assert (((obs - exp) ** 2) / exp).sum() < stats.chi2.ppf(1 - 1e-4, len(deltas) - 1)
+    assert obs.argmax() == len(deltas) - 1                             # the most recent entry is the likeliest
+    probs = _successive_probs(list(inv), 2)
+    big = {s: p for s, p in probs.items() if p * R >= 5}
+    obs2 = np.array([np.sum((o["nbr"][:, 0] == a) & (o["nbr"][:, 1] == b)) for (a, b) in big])
+    exp2 = np.array(list(big.values())) * R
+    assert (((obs2 - exp2) ** 2) / exp2).sum() < stats.chi2.ppf(1 - 1e-4, len(exp2))
+
+
+def test_inverse_timespan_special_cases():
+    """Equal deltas reduce to the uniform law; cnt <= k returns everything, most recent first;
+    entries at or after t are never drawn; deltas beyond 2^32 still get weight 1 (never 0);
+    extreme timestamps do not overflow."""
+    t = 777
+    g = _timed_node([700] * 5)                                          # five entries, same delta
+    R = 100000
+    o = oracle.sample_hop(g, np.zeros(R, np.int32), np.full(R, t, np.int64), 2, oracle.INVERSE_TIMESPAN, 3, 0,
+                          threads=4)
+    code = o["nbr"][:, 0] * 5 + o["nbr"][:, 1]
+    pairs = [a * 5 + b for a in range(5) for b in range(5) if a != b]
+    obs = np.bincount(code, minlength=25)[pairs]
+    assert obs.sum() == R
+    assert (((obs - R / 20) ** 2) / (R / 20)).sum() < stats.chi2.ppf(1 - 1e-4, 19)
+
+    g = _timed_node([10, 20, 30])
+    o = oracle.sample_hop(g, np.zeros(2, np.int32), np.array([31, 25], np.int64), 4, oracle.INVERSE_TIMESPAN, 1, 0)
+    assert o["nbr"].tolist() == [[2, 1, 0, -1], [1, 0, -1, -1]] and o["count"].tolist() == [3, 2]
+
+    far = -(1 << 62)
+    ts_list = [far, far + 1, far + 2, 0, 1 << 40, (1 << 62) - 5]
+    g = _timed_node(ts_list)
+    tq = (1 << 62)                                                      # deltas up to 2^63
+    w = _inverse_weights(ts_list, tq)
+    assert w[:5] == [1, 1, 1, 1, 1] and w[5] == (1 << 32) // 5
+    R = 20000
+    o = oracle.sample_hop(g, np.zeros(R, np.int32), np.full(R, tq, np.int64), 3, oracle.INVERSE_TIMESPAN, 9, 0)
+    assert (o["ts"] < tq).all() and o["nbr"].max() == 5 and o["nbr"].min() == 0
+    first_old = (o["nbr"][:, 0] < 5).mean()
+    p = 5 / (5 + w[5])
+    assert abs(first_old - p) < 5 * np.sqrt(p / R) + 1e-4
+    assert all(len(set(r)) == 3 for r in o["nbr"].tolist())
+
+
+def test_inverse_timespan_two_hops_respect_time():
+    rng = np.random.default_rng(2)
+    n, nodes = 6000, 30
+    src = rng.integers(0, nodes, n).astype(np.int32)
+    dst = rng.integers(0, nodes, n).astype(np.int32)
+    ts = np.sort(rng.integers(0, 10000, n)).astype(np.int64)
+    g = oracle.tcsr_build(src, dst, ts, np.arange(n, dtype=np.int32), nodes)
+    roots = rng.integers(0, nodes, 200).astype(np.int32)
+    times = rng.integers(0, 10000, 200).astype(np.int64)
+    h = oracle.sample_temporal(g, roots, times, 5, 2, oracle.INVERSE_TIMESPAN, seed=4)
+    one = oracle.sample_hop(g, h[0]["nbr"].ravel(), h[0]["ts"].ravel(), 5, oracle.INVERSE_TIMESPAN, 4, 1)
+    for f in ("nbr", "eid", "ts", "count"):
+        assert np.array_equal(h[1][f], one[f])
+    valid = h[0]["eid"] >= 0
+    assert (h[0]["ts"][valid] < np.repeat(times, 5).reshape(-1, 5)[valid]).all()
+    assert np.array_equal(src[h[0]["eid"][valid]], np.repeat(roots, 5).reshape(-1, 5)[valid])
+    v2 = h[1]["eid"] >= 0
+    assert (h[1]["ts"][v2] < np.repeat(h[0]["ts"].ravel(), 5).reshape(-1, 5)[v2]).all()
+
+
+# --------------------------------------------------------------------------- adaptive mini-batch selection
+def test_batch_draw_equals_numpy_inverse_cdf():
+    """Draw j = first index whose cumulative score exceeds floor(draw * W / 2^64):
+    numpy.cumsum + searchsorted(side='right') with the scaling done in Python integers."""
+    rng = np.random.default_rng(6)
+    for n, b in ((1, 5), (7, 50), (5000, 600), (100000, 64)):
+        score = rng.integers(0, 1 << 17, n).astype(np.uint32)
+        score[rng.integers(0, n, n // 3)] = 0
+        if n == 1:
+            score[:] = 9
+        cum = np.cumsum(score.astype(np.uint64))
+        W = int(cum[-1])
+        got = oracle.batch_draw(score, b, seed=31, iteration=12)
+        xs = np.array([(oracle.draw64(31, 0x4253454C, 12, j) * W) >> 64 for j in range(b)], np.uint64)
+        assert np.array_equal(got, np.searchsorted(cum, xs, side="right").astype(np.int32))
+        assert (score[got] > 0).all()                                  # a zero score is never drawn
+        again = oracle.batch_draw(score, b, seed=31, iteration=13)
+        assert n == 1 or not np.array_equal(got, again)                # the iteration number matters
+    assert oracle.batch_draw(np.zeros(4, np.uint32), 3, 1, 0).tolist() == [-1, -1, -1]
+    big = np.full(3, 0xFFFFFFFF, np.uint32)                            # sums beyond 32 bits
+    got = oracle.batch_draw(big, 3000, 2, 0)
+    assert np.bincount(got, minlength=3).min() > 900
+
+
+def test_batch_draw_probability_is_proportional_to_the_score():
+    rng = np.random.default_rng(10)
+    score = np.clip(np.rint((1 / (1 + np.exp(-rng.standard_normal(40))) + 0.1) * 65536), 1, None).astype(np.uint32)
+    b = 200000
+    got = oracle.batch_draw(score, b, seed=3, iteration=0)
+    obs = np.bincount(got, minlength=40)
+    exp = score / score.sum() * b
+    assert (((obs - exp) ** 2) / exp).sum() < stats.chi2.ppf(1 - 1e-4, 39)
+    uniform = np.full(25, 6554, np.uint32)                             # "initialised uniformly"
+    obs = np.bincount(oracle.batch_draw(uniform, b, seed=4, iteration=1), minlength=25)
+    assert (((obs - b / 25) ** 2) / (b / 25)).sum() < stats.chi2.ppf(1 - 1e-4, 24)
+
+
+def test_score_update_is_the_sequential_loop():
+    rng = np.random.default_rng(14)
+    n, b = 300, 1000                                                    # many edges drawn more than once
+    score = rng.integers(1, 1000, n).astype(np.uint32)
+    idx = rng.integers(-3, n + 3, b).astype(np.int32)
+    val = rng.integers(0, 1 << 32, b, dtype=np.uint64).astype(np.uint32)
+    want = score.copy().tolist()
+    for j in range(b):
+        if 0 <= idx[j] < n:
+            want[idx[j]] = int(val[j])
+    oracle.score_update(score, idx, val)
+    assert score.tolist() == want
