@@ -31,6 +31,7 @@ extern "C" {
 
 typedef struct taser_tcsr taser_tcsr;   /* time-sorted CSR in device memory  */
 typedef struct taser_cache taser_cache; /* device cache over a host table    */
+typedef struct taser_selector taser_selector; /* importance scores of the training edges */
 
 enum taser_status {
     TASER_OK = 0,
@@ -291,6 +292,43 @@ int taser_cache_epoch_end(taser_cache* c, int64_t min_overlap, int64_t* overlap,
 int taser_cache_residents(const taser_cache* c, int32_t* resident_ids_host);
 
 void taser_cache_free(taser_cache* c);
+
+/* ---------------------------------------------------------------------------
+ * Adaptive mini-batch selection (Sec. 3.1: a list of importance scores P over
+ * the training edges, initialised uniformly; every iteration samples a batch of
+ * training edges with probability proportional to the scores and afterwards
+ * overwrites the scores of the batch's edges, Eq. (4)).
+ *
+ * Scores are uint32; turning sigmoid(y) + gamma into an integer is the
+ * caller's business (it needs the model's output). The handle keeps the scores
+ * and two levels of partial sums in device memory; a draw or an update costs
+ * time proportional to the batch, not to the number of training edges.
+ *
+ * taser_selector_init: n training edges in [1, 2^31); scores device uint32[n],
+ *   or NULL: every score = initial_score. Synchronizes `hip_stream`.
+ * taser_selector_draw: batch[j], j < b, = the first edge whose running score
+ *   sum (edge 0 first) exceeds floor(draw * W / 2^64), W = the sum of all
+ *   scores, draw = the Philox 4x32-10 draw keyed (seed, hop tag 0x4253454C,
+ *   root index `iteration`, slot j): b independent draws, so an edge can appear
+ *   twice; an edge with score 0 is never drawn; W == 0 gives -1.
+ *   batch device int32[b], b in [0, 2^31).
+ * taser_selector_update: score[batch[j]] = new_scores[j] for j = 0..b-1 in that
+ *   order (an edge named twice keeps the later value); entries outside [0, n)
+ *   are skipped. batch device int32[b], new_scores device uint32[b]. Must be
+ *   ordered after the draws that should see the old scores.
+ * taser_selector_scores: copies the scores to `scores` (device uint32[n], may
+ *   be NULL); if `total` (host, may be NULL) is given it receives the sum of
+ *   all scores as the partial sums hold it, and the call synchronizes.
+ * ------------------------------------------------------------------------- */
+int taser_selector_init(const uint32_t* scores, int64_t n, uint32_t initial_score, void* hip_stream,
+                        taser_selector** out);
+int taser_selector_draw(const taser_selector* s, int64_t b, uint64_t seed, uint64_t iteration,
+                        int32_t* batch, void* hip_stream);
+int taser_selector_update(taser_selector* s, const int32_t* batch, const uint32_t* new_scores, int64_t b,
+                          void* hip_stream);
+int taser_selector_scores(const taser_selector* s, uint32_t* scores, uint64_t* total, void* hip_stream);
+int taser_selector_size(const taser_selector* s, int64_t* n);
+void taser_selector_free(taser_selector* s);
 
 /* ---------------------------------------------------------------------------
  * Optional per-kernel timing, for benchmarks. Between taser_profile_begin and

@@ -21,7 +21,8 @@ MAX_K, MAX_M, MAX_HOPS = 64, 64, 3
 EXPORTS = ("taser_tcsr_build", "taser_tcsr_size", "taser_tcsr_view", "taser_tcsr_free", "taser_sample_temporal",
            "taser_candidate_encodings", "taser_select_weighted", "taser_gather_features", "taser_cache_init", "taser_cache_lookup", "taser_cache_prefetch", "taser_cache_gather", "taser_cache_tune", "taser_cache_count_accesses", "taser_cache_access_counts",
            "taser_cache_epoch_end", "taser_cache_residents",
-           "taser_cache_free", "taser_profile_begin", "taser_profile_end", "taser_last_error")
+           "taser_cache_free", "taser_selector_init", "taser_selector_draw", "taser_selector_update",
+           "taser_selector_scores", "taser_selector_size", "taser_selector_free", "taser_profile_begin", "taser_profile_end", "taser_last_error")
 
 
 class TaserError(RuntimeError):
@@ -73,6 +74,13 @@ def lib():
         L.taser_cache_residents.argtypes = [vp, vp]
         L.taser_cache_free.argtypes = [vp]
         L.taser_cache_free.restype = None
+        L.taser_selector_init.argtypes = [vp, i64, u32, vp, ctypes.POINTER(vp)]
+        L.taser_selector_draw.argtypes = [vp, i64, u64, u64, vp, vp]
+        L.taser_selector_update.argtypes = [vp, vp, vp, i64, vp]
+        L.taser_selector_scores.argtypes = [vp, vp, ctypes.POINTER(u64), vp]
+        L.taser_selector_size.argtypes = [vp, ctypes.POINTER(i64)]
+        L.taser_selector_free.argtypes = [vp]
+        L.taser_selector_free.restype = None
         L.taser_profile_begin.argtypes = []
         L.taser_profile_end.argtypes = [ctypes.POINTER(_KernelTime), i32, ctypes.POINTER(i32)]
         L.taser_last_error.restype = ctypes.c_char_p
@@ -360,6 +368,74 @@ def cache_residents(c):
 
 def cache_free(c):
     c.free()
+
+
+class Selector:
+    """Owner of a taser_selector handle."""
+
+    def __init__(self, handle, n):
+        self.handle, self.n = handle, n
+
+    def free(self):
+        if self.handle:
+            lib().taser_selector_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def selector_init(scores=None, n=None, initial_score=1, stream=None):
+    """taser_selector_init. scores: device int32 tensor holding uint32 bits, or None with n."""
+    if scores is not None:
+        _want(scores, torch.int32, "scores (uint32 bits in an int32 tensor)")
+        n = scores.numel()
+    h = ctypes.c_void_p()
+    _check(lib().taser_selector_init(_ptr(scores), n, initial_score, _stream(stream), ctypes.byref(h)))
+    return Selector(h, n)
+
+
+def selector_draw(s, b, seed, iteration, out=None, stream=None):
+    """taser_selector_draw -> device int32[b] edge indices."""
+    if out is None:
+        out = torch.empty(b, dtype=torch.int32, device="cuda")
+    else:
+        _want(out, torch.int32, "out")
+        if out.numel() < b:
+            raise ValueError("out is too small")
+    _check(lib().taser_selector_draw(s.handle, b, seed, iteration, _ptr(out), _stream(stream)))
+    return out
+
+
+def selector_update(s, batch, new_scores, stream=None):
+    """taser_selector_update."""
+    _want(batch, torch.int32, "batch")
+    _want(new_scores, torch.int32, "new_scores (uint32 bits in an int32 tensor)")
+    if batch.numel() != new_scores.numel():
+        raise ValueError("batch and new_scores must have the same length")
+    _check(lib().taser_selector_update(s.handle, _ptr(batch), _ptr(new_scores), batch.numel(), _stream(stream)))
+
+
+def selector_scores(s, want_total=True, stream=None):
+    """taser_selector_scores -> (device int32[n] holding the uint32 scores, total or None)."""
+    out = torch.empty(s.n, dtype=torch.int32, device="cuda")
+    total = ctypes.c_uint64()
+    _check(lib().taser_selector_scores(s.handle, _ptr(out), ctypes.byref(total) if want_total else None,
+                                       _stream(stream)))
+    return out, (int(total.value) if want_total else None)
+
+
+def selector_size(s):
+    n = ctypes.c_int64()
+    _check(lib().taser_selector_size(s.handle, ctypes.byref(n)))
+    return n.value
+
+
+def selector_free(s):
+    s.free()
 
 
 def profile_begin():

@@ -529,3 +529,49 @@ def test_cache_epoch_end_ties_and_extremes():
             assert out.cpu().numpy().tobytes() == host_np.tobytes()
             assert tuple(hm.tolist()) == (cap, rows - cap)
             oracle.cache_count(probe, rows, Q)
+
+
+# ----------------------------------------------------------------------------- adaptive mini-batch selection
+@pytest.mark.parametrize("n", [1, 63, 1024, 1025, 70000, (1 << 20) + 5, 3_000_000])
+def test_selector_draws_and_updates_match_the_oracle(n):
+    """Several iterations of draw -> update (with edges named twice, padding and out-of-range
+    entries), sizes around the partial-sum boundaries (1024, 1024^2)."""
+    rng = np.random.default_rng(n)
+    score = rng.integers(0, 1 << 17, n, dtype=np.uint64).astype(np.uint32)
+    score[rng.integers(0, n, n // 4)] = 0
+    if n > 2000:
+        score[1024:2048] = 0                                       # a whole level-1 block of zeros
+        score[-3:] = 0xFFFFFFFF
+    score[0] = max(score[0], 1)
+    s = T.selector_init(dev(score.view(np.int32)))
+    assert T.selector_size(s) == n
+    for it, b in enumerate((600, 1, 4000, 65)):
+        want = oracle.batch_draw(score, b, seed=11, iteration=it)
+        got = T.selector_draw(s, b, 11, it)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), want)
+        idx = want.copy()
+        idx[::7] = idx[0]                                          # the same edge several times: the last value stays
+        idx[3::11] = -1
+        idx[5::13] = n + 2
+        val = rng.integers(0, 1 << 32, b, dtype=np.uint64).astype(np.uint32)
+        val[::5] = 0
+        oracle.score_update(score, idx, val)
+        T.selector_update(s, dev(idx), dev(val.view(np.int32)))
+        got_scores, total = T.selector_scores(s)
+        assert np.array_equal(got_scores.cpu().numpy().view(np.uint32), score)
+        assert total == int(score.astype(np.uint64).sum())
+    T.selector_free(s)
+
+
+def test_selector_uniform_start_and_all_zero():
+    s = T.selector_init(n=5000, initial_score=6554)
+    want = oracle.batch_draw(np.full(5000, 6554, np.uint32), 600, seed=1, iteration=0)
+    assert np.array_equal(T.selector_draw(s, 600, 1, 0).cpu().numpy(), want)
+    every = torch.arange(5000, dtype=torch.int32, device="cuda")
+    T.selector_update(s, every, torch.zeros(5000, dtype=torch.int32, device="cuda"))
+    assert T.selector_draw(s, 10, 1, 1).tolist() == [-1] * 10
+    assert T.selector_scores(s)[1] == 0
+    one = torch.tensor([4321], dtype=torch.int32, device="cuda")
+    T.selector_update(s, one, torch.tensor([-1], dtype=torch.int32, device="cuda"))     # 2^32 - 1
+    assert T.selector_draw(s, 10, 1, 2).tolist() == [4321] * 10

@@ -102,6 +102,20 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert lib.taser_cache_access_counts(None, one, None) == E_ARG
     assert lib.taser_cache_epoch_end(None, 1, None, None, None) == E_ARG
     assert lib.taser_cache_residents(None, None) == E_ARG
+    sel = ctypes.c_void_p()
+    assert lib.taser_selector_init(None, 0, 1, None, ctypes.byref(sel)) == E_RANGE
+    assert lib.taser_selector_init(None, 2 ** 31, 1, None, ctypes.byref(sel)) == E_RANGE
+    assert lib.taser_selector_init(None, 5, 1, None, None) == E_ARG
+    assert lib.taser_selector_draw(None, 5, 0, 0, one, None) == E_ARG
+    assert lib.taser_selector_draw(one, -1, 0, 0, one, None) == E_RANGE
+    assert lib.taser_selector_draw(one, 5, 0, 0, None, None) == E_ARG
+    assert lib.taser_selector_draw(one, 0, 0, 0, None, None) == 0
+    assert lib.taser_selector_update(None, one, one, 5, None) == E_ARG
+    assert lib.taser_selector_update(one, None, one, 5, None) == E_ARG
+    assert lib.taser_selector_update(one, one, one, 2 ** 31, None) == E_RANGE
+    assert lib.taser_selector_scores(None, one, None, None) == E_ARG
+    assert lib.taser_selector_size(None, None) == E_ARG
+    lib.taser_selector_free(None)
     n = ctypes.c_int32()
     assert lib.taser_profile_end(None, 4, ctypes.byref(n)) == E_ARG
     lib.taser_tcsr_free(None)
