@@ -45,7 +45,9 @@ enum taser_status {
 enum taser_policy {
     TASER_RECENT = 0,   /* most recent neighbor finder   (Sec. 2.1, Alg. 2)              */
     TASER_UNIFORM = 1,  /* uniform, without replacement  (Sec. 2.1, Alg. 2)              */
-    TASER_WEIGHTED = 2  /* n of the m most recent, by given weights (Alg. 1, 2nd draw)   */
+    TASER_WEIGHTED = 2, /* n of the m most recent, by given weights (Alg. 1, 2nd draw)   */
+    TASER_INVERSE_TIMESPAN = 3 /* probability inversely proportional to the time delta:
+                                  the heuristic finder of TGAT (Sec. 1, Sec. 2.3)        */
 };
 
 enum taser_build_flags {
@@ -113,6 +115,12 @@ void taser_tcsr_free(taser_tcsr* g);
  *                   replacement, each proportional to the remaining weights:
  *                   x = floor(draw * W / 2^64), first remaining candidate
  *                   whose running weight sum exceeds x.
+ *   TASER_INVERSE_TIMESPAN  over all cnt valid entries, entry p weighs
+ *                   max(1, floor(2^32 / (t - ts[p]))). cnt <= k: as
+ *                   TASER_RECENT. Otherwise k successive draws without
+ *                   replacement as for TASER_WEIGHTED, the running sum taken
+ *                   in list order (oldest entry first). Costs time linear in
+ *                   cnt per root (the weights depend on the query time).
  * count[i] = number of filled (leading) slots; the rest are padding.
  * Hop h+1 has one root per slot of hop h, root index i*k + j, node = the
  * sampled neighbor and query time = the sampled interaction's timestamp; a

@@ -14,7 +14,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtaser.so")
 
-RECENT, UNIFORM, WEIGHTED = 0, 1, 2
+RECENT, UNIFORM, WEIGHTED, INVERSE_TIMESPAN = 0, 1, 2, 3
 INPUT_ON_DEVICE = 1
 MAX_K, MAX_M, MAX_HOPS = 64, 64, 3
 

@@ -168,6 +168,166 @@ __global__ __launch_bounds__(kThreads) void sample_hop_kernel(
     if (live && sub == 0) o_count[q] = filled;
 }
 
+// ---- inverse-timespan finder -------------------------------------------------
+// Weight of an entry at time ts for a query at t > ts: max(1, floor(2^32 / (t - ts))).
+__device__ __forceinline__ uint64_t inverse_timespan_weight(int64_t t, int64_t ts) {
+    const uint64_t delta = (uint64_t)t - (uint64_t)ts;   // exact difference, >= 1
+    if (delta >> 32) return 1;                           // the quotient is 1 (delta = 2^32) or 0
+    const uint32_t d = (uint32_t)delta;
+    const uint32_t q = 0xFFFFFFFFu / d, r = 0xFFFFFFFFu - q * d;   // 2^32 = (2^32 - 1) + 1
+    return (uint64_t)q + (r == d - 1u ? 1u : 0u);
+}
+
+__device__ __forceinline__ uint64_t wave_sum64(uint64_t v) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const uint32_t lo = __shfl_xor((uint32_t)v, d, kWave);
+        const uint32_t hi = __shfl_xor((uint32_t)(v >> 32), d, kWave);
+        v += ((uint64_t)hi << 32) | lo;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint64_t wave_inclusive_scan64(uint64_t v, int lane) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const uint32_t lo = __shfl_up((uint32_t)v, d, kWave);
+        const uint32_t hi = __shfl_up((uint32_t)(v >> 32), d, kWave);
+        if (lane >= d) v += ((uint64_t)hi << 32) | lo;
+    }
+    return v;
+}
+
+constexpr int kTileRows = 8;                      // registers of tile sums per lane
+constexpr int kMaxTiles = kTileRows * kWave;      // tile sums per root
+
+// One wavefront per root: the weights 1/(t - ts) depend on the query, so the whole
+// valid list has to be read once per root. The list is cut into at most 512 tiles
+// of whole 64-entry rows; pass 1 leaves every tile's weight sum in a register
+// (tile i in lane i % 64, register i / 64). Each of the k draws then walks the tile
+// sums, re-reads only the tile it lands in, and takes the picked weight out of the
+// tile's sum, so a draw costs one tile, not the list.
+__global__ __launch_bounds__(kThreads) void sample_hop_inverse_timespan_kernel(
+    const int64_t* __restrict__ indptr, const TaserRec* __restrict__ rec, const int32_t* __restrict__ roots,
+    const int64_t* __restrict__ times, int64_t num_roots, int32_t num_nodes, int k, uint32_t seed_lo, uint32_t seed_hi,
+    uint32_t hop, int32_t* __restrict__ o_nbr, int32_t* __restrict__ o_eid, int64_t* __restrict__ o_ts,
+    int32_t* __restrict__ o_count) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t q = (int64_t)blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
+    if (q >= num_roots) return;   // wave-uniform; the kernel has no block-wide barrier
+
+    int64_t lo = 0, hi = 0, t = 0;
+    const int32_t v = roots[q];
+    if (v >= 0 && v < num_nodes) {
+        t = times[q];
+        lo = indptr[v];
+        hi = indptr[v + 1];
+    }
+    const int64_t cnt = group_cutoff<kWave>(rec, lo, hi, t, 0, lane);
+    const int64_t out0 = q * k;
+    const TaserRec pad = {0, -1, -1};
+    if (cnt <= k) {   // everything, most recent first
+        if (lane < k) store_slot(o_nbr, o_eid, o_ts, out0 + lane, lane < cnt ? rec[lo + cnt - 1 - lane] : pad);
+        if (lane == 0) o_count[q] = (int32_t)cnt;
+        return;
+    }
+
+    const int64_t rows = (cnt + kWave - 1) / kWave;                 // 64-entry rows of the valid list
+    const int64_t rows_per_tile = (rows + kMaxTiles - 1) / kMaxTiles;
+    const int tiles = (int)((rows + rows_per_tile - 1) / rows_per_tile);
+    const int tile_rows = (tiles + kWave - 1) / kWave;              // registers in use
+
+    // Pass 1: tile sums.
+    uint64_t tile_sum[kTileRows];
+#pragma unroll
+    for (int i = 0; i < kTileRows; ++i) tile_sum[i] = 0;
+    uint64_t total = 0;
+    for (int tile = 0; tile < tiles; ++tile) {
+        const int64_t r0 = (int64_t)tile * rows_per_tile;
+        const int64_t r1 = r0 + rows_per_tile < rows ? r0 + rows_per_tile : rows;
+        uint64_t s = 0;
+        int64_t r = r0;
+        for (; r + 4 <= r1; r += 4) {   // four independent loads in flight
+            int64_t ts4[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int64_t p = (r + i) * kWave + lane;
+                ts4[i] = rec[lo + (p < cnt ? p : cnt - 1)].ts;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if ((r + i) * kWave + lane < cnt) s += inverse_timespan_weight(t, ts4[i]);
+        }
+        for (; r < r1; ++r) {
+            const int64_t p = r * kWave + lane;
+            if (p < cnt) s += inverse_timespan_weight(t, rec[lo + p].ts);
+        }
+        s = wave_sum64(s);
+        total += s;
+#pragma unroll
+        for (int i = 0; i < kTileRows; ++i)
+            if (i == (tile >> 6) && lane == (tile & (kWave - 1))) tile_sum[i] = s;
+    }
+
+    // k successive draws; lane j keeps the position picked by draw j.
+    uint64_t u = 0;
+    if (lane < k) u = draw64(seed_lo, seed_hi, hop, (uint64_t)q, (uint32_t)lane);
+    int64_t my_pick = 0;
+    for (int j = 0; j < k; ++j) {
+        uint64_t x = __umul64hi(group_get64<kWave>(u, j), total);
+        // the tile whose running sum first exceeds x
+        uint64_t before = 0;
+        int tile = -1;
+#pragma unroll
+        for (int i = 0; i < kTileRows; ++i) {
+            if (i < tile_rows && tile < 0) {
+                const uint64_t inc = wave_inclusive_scan64(tile_sum[i], lane);
+                const uint64_t hit = __ballot(before + inc > x);
+                if (hit) {
+                    const int first = __ffsll((long long)hit) - 1;
+                    x -= before + group_get64<kWave>(inc - tile_sum[i], first);
+                    tile = i * kWave + first;
+                } else {
+                    before += group_get64<kWave>(inc, kWave - 1);
+                }
+            }
+        }
+        if (tile < 0) tile = tiles - 1;   // cannot happen while the sums are consistent (x < total); keeps reads in bounds
+        // inside the tile, row by row; entries picked by earlier draws weigh nothing
+        const int64_t r0 = (int64_t)tile * rows_per_tile;
+        const int64_t r1 = r0 + rows_per_tile < rows ? r0 + rows_per_tile : rows;
+        before = 0;
+        int64_t pick = -1;
+        uint64_t pick_w = 0;
+        for (int64_t r = r0; r < r1 && pick < 0; ++r) {
+            const int64_t p = r * kWave + lane;
+            uint64_t w = 0;
+            if (p < cnt) w = inverse_timespan_weight(t, rec[lo + p].ts);
+            for (int e = 0; e < j; ++e) {
+                const uint64_t taken = group_get64<kWave>((uint64_t)my_pick, e);
+                if ((uint64_t)p == taken) w = 0;
+            }
+            const uint64_t inc = wave_inclusive_scan64(w, lane);
+            const uint64_t hit = __ballot(before + inc > x);
+            if (hit) {
+                const int first = __ffsll((long long)hit) - 1;
+                pick = r * kWave + first;
+                pick_w = group_get64<kWave>(w, first);
+            } else {
+                before += group_get64<kWave>(inc, kWave - 1);
+            }
+        }
+        if (pick < 0) pick = cnt - 1;     // same remark
+        if (lane == j) my_pick = pick;
+        total -= pick_w;
+#pragma unroll
+        for (int i = 0; i < kTileRows; ++i)
+            if (i == (tile >> 6) && lane == (tile & (kWave - 1))) tile_sum[i] -= pick_w;
+    }
+    if (lane < k) store_slot(o_nbr, o_eid, o_ts, out0 + lane, rec[lo + my_pick]);
+    if (lane == 0) o_count[q] = k;
+}
+
 template <int POLICY, int G>
 void launch_hop_g(const taser_tcsr* g, const int32_t* roots, const int64_t* times, int64_t n, int k,
                   uint64_t seed, uint32_t hop, int m, const uint32_t* edge_weight, const taser_hop_out& o,
@@ -202,7 +362,7 @@ extern "C" int taser_sample_temporal(const taser_tcsr* g, const int32_t* roots, 
     if (num_roots > 0 && (!roots || !times)) return taser_fail(TASER_E_ARG, "sample_temporal: null roots/times");
     if (k < 1 || k > TASER_MAX_K) return taser_fail(TASER_E_RANGE, "sample_temporal: k = %d outside [1, %d]", k, TASER_MAX_K);
     if (hops < 1 || hops > TASER_MAX_HOPS) return taser_fail(TASER_E_RANGE, "sample_temporal: hops = %d outside [1, %d]", hops, TASER_MAX_HOPS);
-    if (policy != TASER_RECENT && policy != TASER_UNIFORM && policy != TASER_WEIGHTED)
+    if (policy != TASER_RECENT && policy != TASER_UNIFORM && policy != TASER_WEIGHTED && policy != TASER_INVERSE_TIMESPAN)
         return taser_fail(TASER_E_ARG, "sample_temporal: unknown policy %d", policy);
     if (policy == TASER_WEIGHTED) {
         if (m < 1 || m > TASER_MAX_M) return taser_fail(TASER_E_RANGE, "sample_temporal: m = %d outside [1, %d]", m, TASER_MAX_M);
@@ -224,6 +384,14 @@ extern "C" int taser_sample_temporal(const taser_tcsr* g, const int32_t* roots, 
         switch (policy) {
             case TASER_RECENT: launch_hop<TASER_RECENT>(g, cur_roots, cur_times, n, k, seed, (uint32_t)h, m, edge_weight, out[h], stream); break;
             case TASER_UNIFORM: launch_hop<TASER_UNIFORM>(g, cur_roots, cur_times, n, k, seed, (uint32_t)h, m, edge_weight, out[h], stream); break;
+            case TASER_INVERSE_TIMESPAN: {
+                TaserProfileSpan span(stream, "sample_hop_inverse_timespan");
+                const unsigned grid = (unsigned)((n + kThreads / kWave - 1) / (kThreads / kWave));
+                hipLaunchKernelGGL(sample_hop_inverse_timespan_kernel, dim3(grid), dim3(kThreads), 0, stream, g->indptr, g->rec,
+                                   cur_roots, cur_times, n, g->num_nodes, k, (uint32_t)seed, (uint32_t)(seed >> 32),
+                                   (uint32_t)h, out[h].nbr, out[h].eid, out[h].ts, out[h].count);
+                break;
+            }
             default: launch_hop<TASER_WEIGHTED>(g, cur_roots, cur_times, n, k, seed, (uint32_t)h, m, edge_weight, out[h], stream); break;
         }
         cur_roots = out[h].nbr;

@@ -255,6 +255,50 @@ def test_sampler_is_deterministic_and_independent_of_batch_split():
     assert torch.equal(a[0]["count"], c[0]["count"])
 
 
+# ----------------------------------------------------------------------------- inverse-timespan finder
+@pytest.mark.parametrize("k", [1, 10, 64])
+def test_inverse_timespan_matches_the_oracle(k):
+    """Lists from empty to tens of thousands of entries (one and several rows per tile),
+    ties, three hops for small k, invalid roots."""
+    rng = np.random.default_rng(50 + k)
+    n_nodes, n = 40, 120000
+    src, dst, ts, eid = _graph(rng, n_nodes, n, 50000)
+    src = np.minimum(src, rng.integers(0, n_nodes, n)).astype(np.int32)
+    src[:40000] = 0                                                     # one list of > 40 000 entries: > 512 rows
+    src[src == 7] = 8
+    g, g_ref = build_both(src, dst, ts, eid, n_nodes)
+    roots = rng.integers(0, n_nodes, 400).astype(np.int32)
+    roots[::9] = 0
+    roots[::50] = -1
+    times = rng.integers(-5, 50100, 400).astype(np.int64)
+    hops = 3 if k == 1 else (2 if k == 10 else 1)
+    run_both(g, g_ref, roots, times, k, hops, T.INVERSE_TIMESPAN, seed=0x1234567890ABCDEF)
+
+
+def test_inverse_timespan_long_list_and_extreme_deltas():
+    """A 300 000-entry list (several rows per tile), query times on / between / outside the
+    timestamps, time deltas from 1 to beyond 2^32 (weight 1) and int64 extremes."""
+    rng = np.random.default_rng(9)
+    n = 300_000
+    src = np.zeros(n, np.int32)
+    src[-4000:] = 1
+    dst = rng.integers(0, 3, n).astype(np.int32)
+    ts = np.sort(np.concatenate([rng.integers(-(1 << 62), -(1 << 61), 1000), rng.integers(0, 1 << 34, n - 1000)]))
+    ts = ts.astype(np.int64)
+    g, g_ref = build_both(src, dst, ts, np.arange(n, dtype=np.int32), 3)
+    times = np.concatenate([ts[rng.integers(0, n, 150)] + rng.integers(0, 3, 150), [1 << 62, -(1 << 62), 5, (1 << 34) + 7]])
+    roots = rng.integers(0, 2, times.shape[0]).astype(np.int32)
+    roots[:100] = 0
+    run_both(g, g_ref, roots, times.astype(np.int64), 10, 1, T.INVERSE_TIMESPAN, seed=3)
+
+
+def test_inverse_timespan_on_the_flights_shaped_workload():
+    w = W.make(4, num_batches=1)
+    g, g_ref = build_both(w.src, w.dst, w.ts, w.eid, w.num_nodes)
+    roots, times = w.batches[0]
+    run_both(g, g_ref, roots[:1000], times[:1000], w.k, 2, T.INVERSE_TIMESPAN, seed=42)
+
+
 # ----------------------------------------------------------------------------- candidate-window products
 @pytest.mark.parametrize("m", [1, 5, 16, 25, 32, 33, 64])
 def test_candidate_encodings_match_the_oracle(m):

@@ -54,6 +54,7 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert lib.taser_sample_temporal(g, one, one, 1, 10, 0, 0, 0, 0, None, out, None) == E_RANGE
     assert lib.taser_sample_temporal(g, one, one, 1, 10, 4, 0, 0, 0, None, out, None) == E_RANGE
     assert lib.taser_sample_temporal(g, one, one, 1, 10, 1, 7, 0, 0, None, out, None) == E_ARG
+    assert lib.taser_sample_temporal(g, one, one, 1, 10, 1, 3, 0, 0, None, out, None) == E_ARG   # policy 3 is known: null buffers
     assert lib.taser_sample_temporal(g, one, one, 1, 10, 1, 2, 0, 0, one, out, None) == E_RANGE   # m = 0
     assert lib.taser_sample_temporal(g, one, one, 1, 10, 1, 2, 0, 25, None, out, None) == E_ARG   # no weights
     assert lib.taser_sample_temporal(g, one, one, 1, 10, 1, 0, 0, 0, None, out, None) == E_ARG    # null out buffers
