@@ -43,6 +43,8 @@ def main():
     ap.add_argument("--edges", type=int, default=None, help="override the event count (smaller = not the named workload)")
     ap.add_argument("--schedule", default="pipeline", choices=["serial", "overlap", "pipeline"])
     ap.add_argument("--stage-blocks", type=int, default=16, help="width of the PCIe staging copy when it runs beside other kernels")
+    ap.add_argument("--policy", default=None, choices=["recent", "uniform", "weighted", "inverse_timespan"],
+                    help="override the workload's selection policy (then it is not the named workload)")
     ap.add_argument("--cpu-roots", type=int, default=6000, help="roots of batch 0 the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -64,6 +66,10 @@ def main():
     kw = {} if args.edges is None else {"edges": args.edges}
     w = W.make(args.config, **kw)
     policy = w.policies[0]
+    if args.policy is not None:
+        policy = ["recent", "uniform", "weighted", "inverse_timespan"].index(args.policy)
+        if policy == 2 and w.edge_weight is None:
+            ap.error("this workload has no edge weights")
     log(f"workload {w.name}: {w.num_nodes} nodes, {w.num_edges} events, generated in {time.time() - t0:.1f}s")
 
     # ------------------------------------------------------------------ resident inputs
@@ -241,6 +247,32 @@ def main():
                        "epoch_end_wall_ms": round(t_epoch * 1e3, 3), "epoch_end_overlap": overlap,
                        "rows": w.num_nodes, "capacity": cache.capacity}
 
+    # ------------------------------------------------------------------ further rows (outside the timed region)
+    # Candidate-window products of the adaptive sampler on this batch's roots (m = 25 most recent
+    # candidates, encodings, 10 of 25 by per-slot weights) and adaptive mini-batch selection over
+    # the 10^6 latest events (the training split the paper uses for its largest dataset).
+    b0 = batches[0]
+    m_c = 25
+    cand = T.sample_temporal(g, b0["roots"], b0["times"], m_c, 1, T.RECENT, 42, stream=main)[0]
+    slot_w = torch.randint(1, 1 << 16, (R, m_c), dtype=torch.int32, device=dev)
+    n_train = min(1_000_000, w.num_edges)
+    selector = T.selector_init(n=n_train, initial_score=6554)
+    new_scores = torch.randint(1, 1 << 17, (R // 3,), dtype=torch.int32, device=dev)
+    for it in range(-2, 20):                     # two untimed passes first
+        if it == 0:
+            torch.cuda.synchronize()
+            T.profile_begin()
+        T.candidate_encodings(cand["nbr"], cand["count"], stream=main)
+        T.select_weighted(slot_w, cand["count"], k, 42, 0, candidates=cand, stream=main)
+        drawn = T.selector_draw(selector, R // 3, 42, it + 2, stream=main)
+        T.selector_update(selector, drawn, new_scores, stream=main)
+    torch.cuda.synchronize()
+    extra = T.profile_end()
+    further = {"roots": R, "m": m_c, "k": k, "training_edges": n_train, "batch_edges": R // 3,
+               "avg_ms": {n: round(ms / c, 4) for n, (c, ms) in extra.items()}}
+    T.selector_free(selector)
+    del cand, slot_w, new_scores
+
     # A plain streaming kernel of known size (out[i] = in[i] + 1 over int32: 1 GiB read +
     # 1 GiB written): under rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings calibrate
     # the counters' unit for the kernels above.
@@ -293,7 +325,7 @@ def main():
         "dtype": "int64", "data": "synthetic",
         "config": {"workload": w.name + ("" if args.edges is None else f" (reduced to {w.num_edges} events)"),
                    "events": w.num_edges, "nodes": w.num_nodes, "roots_per_batch": R, "fanout": [k] * hops,
-                   "policy": ["recent", "uniform", "weighted"][policy], "edge_row_bytes": edge_rb,
+                   "policy": ["recent", "uniform", "weighted", "inverse_timespan"][policy] + ("" if args.policy is None else " (override)"), "edge_row_bytes": edge_rb,
                    "node_row_bytes": node_rb, "distinct_batches": len(batches),
                    "cache_rows": 0 if cache is None else cache.capacity, "schedule": args.schedule},
         "gather_GBps": round(gather_gbps, 1), "gather_frac_of_hbm_peak": round(gather_gbps / HBM_PEAK_GBPS, 4),
@@ -303,7 +335,7 @@ def main():
                        "kernel_ms": round(build_dev_ms, 3),
                        "kernels": {n: round(ms, 3) for n, (_, ms) in build_kernels.items()}},
         "kernels": {n: {"launches": v["launches"], "avg_ms": round(v["avg_ms"], 4)} for n, v in per_kernel.items()},
-        "cache_maintenance": maintenance, "roofline": roofline, "cpu_baseline": cpu,
+        "cache_maintenance": maintenance, "further_rows": further, "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(result), flush=True)
 

@@ -57,6 +57,7 @@ __device__ __forceinline__ uint64_t wave_get64(uint64_t v, int lane) {
 // First index i in [begin, end) whose running sum over a[begin..i] exceeds x, by
 // one wavefront, 64 values per step; x is reduced by the sum before a[i]. The
 // caller guarantees that the whole range sums to more than x. Wave-uniform.
+// Used for the top level, whose length varies.
 template <typename T>
 __device__ __forceinline__ int64_t wave_descend(const T* __restrict__ a, int64_t begin, int64_t end, uint64_t& x,
                                                 int lane) {
@@ -74,6 +75,54 @@ __device__ __forceinline__ int64_t wave_descend(const T* __restrict__ a, int64_t
         before += wave_get64(inc, kWave - 1);
     }
     return end - 1;   // not reached while the guarantee holds
+}
+
+// The same for one group of up to 1024 values starting at a[begin]: lane l loads
+// values 16 l .. 16 l + 15 at once (all loads of the group in flight together),
+// one wave scan of the lane totals finds the lane, that lane walks its 16 values.
+template <typename T>
+__device__ __forceinline__ int64_t wave_descend_group(const T* __restrict__ a, int64_t begin, int64_t end, uint64_t& x,
+                                                      int lane) {
+    constexpr int kPer = kFan / kWave;   // 16
+    T v[kPer];
+    const int64_t mine = begin + (int64_t)lane * kPer;
+    if (begin + kFan <= end) {   // a whole group (wave-uniform): 16-byte loads; the arrays come from hipMalloc and
+                                 // `mine` is a multiple of 16 values, so the address is 64-byte aligned
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        constexpr int kVec = kPer * (int)sizeof(T) / 16;
+        u32x4 raw[kVec];
+        const u32x4* p = reinterpret_cast<const u32x4*>(a + mine);
+#pragma unroll
+        for (int i = 0; i < kVec; ++i) raw[i] = p[i];
+        __builtin_memcpy(v, raw, sizeof(v));
+    } else {
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) v[i] = mine + i < end ? a[mine + i] : (T)0;
+    }
+    uint64_t own = 0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) own += (uint64_t)v[i];
+    const uint64_t inc = wave_inclusive_scan(own, lane);
+    const uint64_t hit = __ballot(inc > x);
+    const int first = hit ? __ffsll((long long)hit) - 1 : kWave - 1;   // hit is never 0 while the guarantee holds
+    uint64_t rest = x - wave_get64(inc - own, first);                  // what is left inside that lane
+    int found = kPer - 1;
+    uint64_t left = rest;
+    bool done = false;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        if (!done) {
+            if ((uint64_t)v[i] > rest) {
+                found = i;
+                left = rest;
+                done = true;
+            } else {
+                rest -= (uint64_t)v[i];
+            }
+        }
+    }
+    x = wave_get64(left, first);
+    return begin + (int64_t)first * kPer + __shfl(found, first, kWave);
 }
 
 // One block per partial sum: out[b] = sum of in[1024*b .. 1024*b+1023].
@@ -118,9 +167,9 @@ __global__ __launch_bounds__(kThreads) void batch_draw_kernel(const uint32_t* __
     uint64_t x = __umul64hi(draw64(seed_lo, seed_hi, kDrawTag, iteration, (uint32_t)j), total);
     const int64_t i2 = wave_descend(sum2, 0, n2, x, lane);
     const int64_t end1 = (i2 + 1) * kFan < n1 ? (i2 + 1) * kFan : n1;
-    const int64_t i1 = wave_descend(sum1, i2 * kFan, end1, x, lane);
+    const int64_t i1 = wave_descend_group(sum1, i2 * kFan, end1, x, lane);
     const int64_t end0 = (i1 + 1) * kFan < n ? (i1 + 1) * kFan : n;
-    const int64_t e = wave_descend(score, i1 * kFan, end0, x, lane);
+    const int64_t e = wave_descend_group(score, i1 * kFan, end0, x, lane);
     if (lane == 0) out[j] = (int32_t)e;
 }
 
@@ -140,16 +189,32 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const int32_t* __restri
                                                          uint32_t* __restrict__ score, uint64_t* __restrict__ sum1,
                                                          uint64_t* __restrict__ sum2, int32_t* __restrict__ owner) {
     const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (j >= b) return;
-    const int32_t e = idx[j];
-    if (e < 0 || e >= n || owner[e] != (int32_t)j) return;
-    const uint32_t old = score[e], now = value[j];
-    score[e] = now;
-    owner[e] = -1;
-    const uint64_t diff = (uint64_t)now - (uint64_t)old;   // modulo 2^64: adding it is the signed change
-    if (diff) {
-        atomicAdd((unsigned long long*)&sum1[e / kFan], (unsigned long long)diff);
-        atomicAdd((unsigned long long*)&sum2[e / (kFan * kFan)], (unsigned long long)diff);
+    const int lane = threadIdx.x & (kWave - 1);
+    uint64_t diff = 0;   // modulo 2^64: adding it is the signed change
+    int32_t e = -1;
+    if (j < b) {
+        e = idx[j];
+        if (e >= 0 && e < n && owner[e] == (int32_t)j) {
+            const uint32_t old = score[e], now = value[j];
+            score[e] = now;
+            owner[e] = -1;
+            diff = (uint64_t)now - (uint64_t)old;
+        }
+    }
+    if (diff) atomicAdd((unsigned long long*)&sum1[e / kFan], (unsigned long long)diff);
+    // A million edges share one level-2 sum: thousands of atomics on one address would
+    // run one after the other. Lanes of a wavefront that change the same level-2 sum
+    // as its first changing lane add up first and issue a single atomic.
+    const uint64_t changing = __ballot(diff != 0);
+    if (changing == 0) return;   // wave-uniform
+    const int leader = __ffsll((long long)changing) - 1;
+    const int32_t top = diff ? e / (kFan * kFan) : -1;
+    const int32_t leader_top = __shfl(top, leader, kWave);
+    const uint64_t together = wave_sum(top == leader_top ? diff : 0);
+    if (lane == leader) {
+        if (together) atomicAdd((unsigned long long*)&sum2[leader_top], (unsigned long long)together);
+    } else if (diff && top != leader_top) {
+        atomicAdd((unsigned long long*)&sum2[top], (unsigned long long)diff);
     }
 }
 

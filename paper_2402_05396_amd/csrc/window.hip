@@ -11,6 +11,8 @@
 // Both kernels use a group of G = 16, 32 or 64 lanes per root (G >= m), one
 // lane per candidate, so a window never leaves registers: comparisons go
 // through lane shuffles, prefix sums through __shfl_up.
+#include <type_traits>
+
 #include "sampling_device.h"
 #include "taser_internal.h"
 
@@ -18,15 +20,22 @@ namespace {
 
 constexpr int kThreads = 256;
 
+// floor(b / d) for small b: d = 1 is the identity, otherwise a multiply-high with
+// magic = ceil(2^32 / d), exact while b * d < 2^32 (here b < 2^13, d <= 2^12).
+__device__ __forceinline__ uint32_t small_div(uint32_t b, uint32_t d, uint32_t magic) {
+    return d == 1u ? b : __umulhi(b, magic);
+}
+
 // freq + identity. Lane j of a group holds u_j and builds a bit mask over l of
 // the candidates equal to it; freq is the mask's population count. The m x m
 // identity bytes of the roots of one wavefront are contiguous in the output,
 // so the wave writes them as one flat range, four bytes per lane and store.
 template <int G>
 __global__ __launch_bounds__(kThreads) void candidate_encodings_kernel(
-    const int32_t* __restrict__ nbr, const int32_t* __restrict__ count, int64_t num_roots, int m,
-    int32_t* __restrict__ freq, uint8_t* __restrict__ identity) {
+    const int32_t* __restrict__ nbr, const int32_t* __restrict__ count, int64_t num_roots, int m, uint32_t magic_m,
+    uint32_t magic_mm, int32_t* __restrict__ freq, uint8_t* __restrict__ identity) {
     constexpr int kGroups = kWave / G;
+    typedef typename std::conditional<(G > 32), uint64_t, uint32_t>::type Mask;   // one bit per candidate
     const int lane = threadIdx.x & (kWave - 1);
     const int group = lane / G, sub = lane % G;
     const int64_t wave_root0 = ((int64_t)blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6)) * kGroups;
@@ -42,43 +51,50 @@ __global__ __launch_bounds__(kThreads) void candidate_encodings_kernel(
     int32_t u = -1;
     if (mine_valid) u = nbr[q * m + sub];
 
-    uint64_t same = 0;   // bit l: candidate l is valid and names the same node as mine
+    Mask same = 0;   // bit l: candidate l is valid and names the same node as mine
     for (int l = 0; l < m; ++l) {
         const int32_t other = (int32_t)group_get<G>((uint32_t)u, l);
-        if (mine_valid && l < c && other == u) same |= (uint64_t)1 << l;
+        if (mine_valid && l < c && other == u) same |= (Mask)1 << l;
     }
-    if (live && sub < m) freq[q * m + sub] = __popcll(same);
+    if (live && sub < m) freq[q * m + sub] = (G > 32) ? __popcll((uint64_t)same) : __popc((uint32_t)same);
 
     if (identity == nullptr) return;   // uniform for the whole grid
-    // Flat byte range of this wave's roots: [first, last). Byte b belongs to root
+    // Flat byte range of this wave's roots: [base, end). Byte b of it belongs to root
     // b / (m*m) of the wave, row (b % (m*m)) / m, column b % m.
     const uint32_t mm = (uint32_t)(m * m);
     int64_t roots_here = num_roots - wave_root0;
     if (roots_here <= 0) return;       // uniform for the wave
     if (roots_here > kGroups) roots_here = kGroups;
     const uint64_t base = (uint64_t)(uintptr_t)identity + (uint64_t)wave_root0 * mm;   // address of the first byte
-    const uint64_t end = base + (uint64_t)roots_here * mm;
-    const uint64_t aligned = base & ~(uint64_t)3;
-    const uint32_t chunks = (uint32_t)((end - aligned + 3) >> 2);
+    const uint32_t length = (uint32_t)roots_here * mm;
+    const uint32_t head = (uint32_t)(base & 3u);          // bytes between the aligned start and base
+    const uint64_t aligned = base - head;
+    const uint32_t chunks = (head + length + 3u) >> 2;
     const uint32_t rounds = (chunks + kWave - 1) / kWave;   // the same for every lane: the shuffles below need them all
     for (uint32_t it = 0; it < rounds; ++it) {
-        const uint64_t at = aligned + ((uint64_t)it * kWave + (uint32_t)lane) * 4u;
+        const uint32_t off = (it * kWave + (uint32_t)lane) * 4u;   // from `aligned`
         uint32_t word = 0;
         bool inside[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const uint64_t p = at + (uint32_t)i;
-            inside[i] = p >= base && p < end;
-            const uint32_t b = inside[i] ? (uint32_t)(p - base) : 0u;
-            const uint32_t r = b / mm, rem = b - r * mm;
-            const uint32_t row = rem / (uint32_t)m, col = rem - row * (uint32_t)m;
+            const uint32_t o = off + (uint32_t)i;
+            inside[i] = o >= head && o < head + length;
+            const uint32_t b = inside[i] ? o - head : 0u;
+            const uint32_t r = small_div(b, mm, magic_mm), rem = b - r * mm;
+            const uint32_t row = small_div(rem, (uint32_t)m, magic_m), col = rem - row * (uint32_t)m;
             // every lane takes part in the shuffle; its source is lane `row` of group r
             const int src = (int)(r * G + row);
-            const uint32_t lo = (uint32_t)__shfl((int)(uint32_t)same, src, kWave);
-            const uint32_t hi = (uint32_t)__shfl((int)(uint32_t)(same >> 32), src, kWave);
-            const uint64_t mask = ((uint64_t)hi << 32) | lo;
+            Mask mask;
+            if (G > 32) {
+                const uint32_t lo = (uint32_t)__shfl((int)(uint32_t)same, src, kWave);
+                const uint32_t hi = (uint32_t)__shfl((int)(uint32_t)((uint64_t)same >> 32), src, kWave);
+                mask = (Mask)(((uint64_t)hi << 32) | lo);
+            } else {
+                mask = (Mask)(uint32_t)__shfl((int)(uint32_t)same, src, kWave);
+            }
             word |= (uint32_t)((mask >> col) & 1u) << (8 * i);
         }
+        const uint64_t at = aligned + off;
         if (inside[0] && inside[3]) {
             *reinterpret_cast<uint32_t*>(at) = word;
         } else {
@@ -166,12 +182,15 @@ extern "C" int taser_candidate_encodings(const int32_t* nbr, const int32_t* coun
     taser_clear_stale_hip_error();
     hipStream_t stream = (hipStream_t)hip_stream;
     TaserProfileSpan span(stream, "candidate_encodings");
+    const uint32_t mm = (uint32_t)(m * m);
+    const uint32_t magic_m = m > 1 ? (uint32_t)((((uint64_t)1 << 32) + (uint32_t)m - 1) / (uint32_t)m) : 0u;
+    const uint32_t magic_mm = m > 1 ? (uint32_t)((((uint64_t)1 << 32) + mm - 1) / mm) : 0u;
     if (m <= 16)
-        hipLaunchKernelGGL((candidate_encodings_kernel<16>), dim3(grid_for<16>(num_roots)), dim3(kThreads), 0, stream, nbr, count, num_roots, m, freq, identity);
+        hipLaunchKernelGGL((candidate_encodings_kernel<16>), dim3(grid_for<16>(num_roots)), dim3(kThreads), 0, stream, nbr, count, num_roots, m, magic_m, magic_mm, freq, identity);
     else if (m <= 32)
-        hipLaunchKernelGGL((candidate_encodings_kernel<32>), dim3(grid_for<32>(num_roots)), dim3(kThreads), 0, stream, nbr, count, num_roots, m, freq, identity);
+        hipLaunchKernelGGL((candidate_encodings_kernel<32>), dim3(grid_for<32>(num_roots)), dim3(kThreads), 0, stream, nbr, count, num_roots, m, magic_m, magic_mm, freq, identity);
     else
-        hipLaunchKernelGGL((candidate_encodings_kernel<64>), dim3(grid_for<64>(num_roots)), dim3(kThreads), 0, stream, nbr, count, num_roots, m, freq, identity);
+        hipLaunchKernelGGL((candidate_encodings_kernel<64>), dim3(grid_for<64>(num_roots)), dim3(kThreads), 0, stream, nbr, count, num_roots, m, magic_m, magic_mm, freq, identity);
     TASER_HIP_TRY(hipGetLastError());
     return TASER_OK;
 }
