@@ -178,19 +178,34 @@ def main():
             main.wait_event(ev_staged[ps])
             T.cache_gather(caches[ps], pb["ids"], out=node_out[ps], stream=main)
 
-    run(0, args.warmup)
+    # Warm-up, with every library kernel bracketed by events: this names the dominant
+    # HBM-bound kernel (the longest of the two gathers; the staging kernel is bound by PCIe
+    # and runs beside them on the side stream).
+    T.profile_begin()
+    run(0, max(args.warmup, 1))
     torch.cuda.synchronize()
+    warm = T.profile_end()
+    dominant = max((n for n in warm if n in ("cache_gather_rows", "gather_rows")), key=lambda n: warm[n][1])
     hit_miss.zero_()
     torch.cuda.synchronize()
 
     # ------------------------------------------------------------------ timed region
-    T.profile_begin()
+    # Only the dominant kernel is bracketed by events here: 16 event records per step on
+    # two streams cost about 5 % of the step, two cost next to nothing.
+    T.profile_begin_only(dominant)
     t0 = time.perf_counter()
     run(0, args.steps)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    kernels = T.profile_end()
+    dominant_time = T.profile_end()[dominant]
     ms_per_step = elapsed * 1e3 / args.steps
+    hm = hit_miss.tolist()
+
+    # The same steps once more with every kernel bracketed, for the per-kernel table.
+    T.profile_begin()
+    run(0, args.steps)
+    torch.cuda.synchronize()
+    kernels = T.profile_end()
 
     # ------------------------------------------------------------------ accounting
     used = [batches[i % len(batches)] for i in range(args.steps)]
@@ -204,25 +219,24 @@ def main():
     gather_gbps = gather_bytes_per_step * args.steps / elapsed / 1e9
 
     per_kernel = {n: {"launches": c, "avg_ms": ms / c} for n, (c, ms) in kernels.items()}
-    # dominant kernel = the longest of the HBM-bound ones (the staging kernel is bound by PCIe and
-    # runs beside them on the side stream)
     hbm_bound = {"cache_gather_rows": node_bytes, "gather_rows": edge_bytes}
     out_bytes = {"cache_gather_rows": n_ids * node_rb, "gather_rows": sum(n_slots) * edge_rb}
-    dominant = max((n for n in kernels if n in hbm_bound), key=lambda n: kernels[n][1], default=None)
     alg_bytes = hbm_bound.get(dominant)
     roofline = None
     if alg_bytes is not None:
-        achieved = alg_bytes / (per_kernel[dominant]["avg_ms"] * 1e-3) / 1e9
+        dom_ms = dominant_time[1] / dominant_time[0]            # measured inside the timed region
+        achieved = alg_bytes / (dom_ms * 1e-3) / 1e9
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                    "avg_launch_ms": round(per_kernel[dominant]["avg_ms"], 4), "algorithmic_bytes": alg_bytes,
+                    "avg_launch_ms": round(dom_ms, 4), "launches_timed": dominant_time[0],
+                    "algorithmic_bytes": alg_bytes,
                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dominant)),
                     "note": "algorithmic bytes = rows x (row read + row written + id); the row reads of this "
                             "kernel are mostly served by L2, so achieved can exceed what HBM alone could carry; "
                             "output_write_GBps is the dense output alone",
-                    "output_write_GBps": round(out_bytes[dominant] / (per_kernel[dominant]["avg_ms"] * 1e-3) / 1e9, 1)}
+                    "output_write_GBps": round(out_bytes[dominant] / (dom_ms * 1e-3) / 1e9, 1)}
         if roofline["traffic"]:
-            t_gbps = roofline["traffic"] / (per_kernel[dominant]["avg_ms"] * 1e-3) / 1e9
+            t_gbps = roofline["traffic"] / (dom_ms * 1e-3) / 1e9
             roofline["traffic_GBps"] = round(t_gbps, 1)               # measured HBM-side bytes / measured time
             roofline["traffic_frac"] = round(t_gbps / HBM_PEAK_GBPS, 4)
 
@@ -317,7 +331,6 @@ def main():
         cpu = {"value": round(cpu_neighbors / (t_sample + t_gather), 1), "unit": "neighbors/s", "cores": threads,
                "kind": "oracle", "sample": sample}
 
-    hm = hit_miss.tolist()
     result = {
         "metric": "sampled temporal neighbors/sec + gather GB/s (% of HBM peak), 2-hop 10x10",
         "value": round(value, 1), "unit": "neighbors/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -335,6 +348,8 @@ def main():
                        "kernel_ms": round(build_dev_ms, 3),
                        "kernels": {n: round(ms, 3) for n, (_, ms) in build_kernels.items()}},
         "kernels": {n: {"launches": v["launches"], "avg_ms": round(v["avg_ms"], 4)} for n, v in per_kernel.items()},
+        "kernels_note": "per-kernel times from a second pass of the same steps with every kernel bracketed by events; "
+                        "the roofline kernel's time is from the timed region itself",
         "cache_maintenance": maintenance, "further_rows": further, "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(result), flush=True)

@@ -347,6 +347,10 @@ void taser_selector_free(taser_selector* s);
  * distinct kernel: its name (static storage), number of launches and summed
  * device time in milliseconds; *num_entries receives the number of entries.
  * At most 65536 launches are recorded per session; later ones are not timed.
+ * taser_profile_begin_only(kernel_name) starts a session that brackets only the
+ * kernel of that name (as reported by an earlier session; NULL or "" = all):
+ * every event pair costs a few microseconds of stream time, which matters when
+ * the whole pass is being timed as well.
  * ------------------------------------------------------------------------- */
 typedef struct taser_kernel_time {
     const char* name;
@@ -355,6 +359,7 @@ typedef struct taser_kernel_time {
 } taser_kernel_time;
 
 int taser_profile_begin(void);
+int taser_profile_begin_only(const char* kernel_name);
 int taser_profile_end(taser_kernel_time* out, int32_t max_entries, int32_t* num_entries);
 
 /* Message for the most recent error on the calling thread (static storage). */

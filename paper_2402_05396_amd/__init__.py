@@ -22,7 +22,7 @@ EXPORTS = ("taser_tcsr_build", "taser_tcsr_size", "taser_tcsr_view", "taser_tcsr
            "taser_candidate_encodings", "taser_select_weighted", "taser_gather_features", "taser_cache_init", "taser_cache_lookup", "taser_cache_prefetch", "taser_cache_gather", "taser_cache_tune", "taser_cache_count_accesses", "taser_cache_access_counts",
            "taser_cache_epoch_end", "taser_cache_residents",
            "taser_cache_free", "taser_selector_init", "taser_selector_draw", "taser_selector_update",
-           "taser_selector_scores", "taser_selector_size", "taser_selector_free", "taser_profile_begin", "taser_profile_end", "taser_last_error")
+           "taser_selector_scores", "taser_selector_size", "taser_selector_free", "taser_profile_begin", "taser_profile_begin_only", "taser_profile_end", "taser_last_error")
 
 
 class TaserError(RuntimeError):
@@ -82,6 +82,7 @@ def lib():
         L.taser_selector_free.argtypes = [vp]
         L.taser_selector_free.restype = None
         L.taser_profile_begin.argtypes = []
+        L.taser_profile_begin_only.argtypes = [ctypes.c_char_p]
         L.taser_profile_end.argtypes = [ctypes.POINTER(_KernelTime), i32, ctypes.POINTER(i32)]
         L.taser_last_error.restype = ctypes.c_char_p
         _lib = L
@@ -441,6 +442,11 @@ def selector_free(s):
 def profile_begin():
     """taser_profile_begin: start timing every kernel the library launches."""
     _check(lib().taser_profile_begin())
+
+
+def profile_begin_only(kernel_name):
+    """taser_profile_begin_only: time only the kernel of this name."""
+    _check(lib().taser_profile_begin_only(kernel_name.encode() if kernel_name else None))
 
 
 def profile_end(max_entries=64):

@@ -2,6 +2,7 @@
 // taser_profile_end() every kernel the library launches is bracketed by a pair
 // of HIP events recorded on the stream it is launched on.
 #include <cstring>
+#include <string>
 #include <vector>
 
 #include "taser_internal.h"
@@ -14,6 +15,7 @@ struct Span {
 };
 
 bool g_enabled = false;
+std::string g_only;               // non-empty: time only the kernel of this name
 std::vector<Span> g_spans;        // spans of the current session
 std::vector<hipEvent_t> g_pool;   // events free for reuse
 constexpr size_t kMaxSpans = 1u << 16;
@@ -33,6 +35,7 @@ hipEvent_t take_event() {
 
 TaserProfileSpan::TaserProfileSpan(hipStream_t stream, const char* name) : stream_(stream), index_(-1) {
     if (!g_enabled || g_spans.size() >= kMaxSpans) return;
+    if (!g_only.empty() && g_only != name) return;
     Span s{take_event(), take_event(), name};
     if (!s.start || !s.stop) return;
     if (hipEventRecord(s.start, stream) != hipSuccess) return;
@@ -44,7 +47,14 @@ TaserProfileSpan::~TaserProfileSpan() {
     if (index_ >= 0) (void)hipEventRecord(g_spans[(size_t)index_].stop, stream_);
 }
 
+extern "C" int taser_profile_begin_only(const char* kernel_name) {
+    const int rc = taser_profile_begin();
+    g_only = kernel_name ? kernel_name : "";
+    return rc;
+}
+
 extern "C" int taser_profile_begin(void) {
+    g_only.clear();
     for (const Span& s : g_spans) {
         g_pool.push_back(s.start);
         g_pool.push_back(s.stop);

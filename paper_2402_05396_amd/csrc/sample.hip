@@ -24,36 +24,49 @@
 
 namespace {
 
-// Number of entries in [lo, hi) with ts < t, for a time-sorted list: a (G+1)-ary
-// search. Every round the G lanes of a group probe G pivots that cut the open
-// range into G+1 nearly equal parts and a ballot narrows it. Groups of one wave
-// run different numbers of rounds; a finished group idles. lo, hi, t are uniform
-// inside a group; every lane of the wave must call this.
+// Number of entries in [lo, hi) with ts < t, for a time-sorted list [lo, hi) of the
+// record array: the first position p* in [lo, hi] that is not "before", where
+// before(p) = p < lo, or p < hi and ts[p] < t (monotone over the whole array).
+// The search descends the levels of the time index. Entry i of level L stands for
+// the positions [i 16^L, (i+1) 16^L) and holds the timestamp of the last of them;
+// p* lies in the first entry whose last position is not before. A group starts at
+// the lowest level at which its list touches at most 16 entries, then reads one
+// aligned block of 16 entries (one 128-byte line) per level down to the records
+// themselves (level 0). 16 lanes of the group probe; whether a position is below
+// lo or at/after hi is known without reading it. Groups of one wave start at
+// different levels under one wave-uniform loop. lo, hi, t are uniform inside a
+// group; every lane of the wave must call this.
 template <int G>
-__device__ __forceinline__ int64_t group_cutoff(const TaserRec* __restrict__ rec, int64_t lo, int64_t hi,
-                                                int64_t t, int group, int sub) {
-    int64_t a = lo, b = hi;   // entries before a are < t, entries from b on are >= t
-    bool wide = b - a > G;
-    while (__ballot(wide)) {
-        // pivot i (1-based) sits at a + floor(len * i / (G+1)), computed as
-        // q*i + floor(r*i/(G+1)) so that everything stays in 32 bits (len < 2^31)
-        const uint32_t len = (uint32_t)(b - a);
-        const uint32_t q = len / (uint32_t)(G + 1), r = len - q * (uint32_t)(G + 1);
-        auto pivot = [&](uint32_t i1) { return a + (int64_t)(q * i1 + (r * i1) / (uint32_t)(G + 1)); };
-        bool before = false;
-        if (wide) before = rec[pivot((uint32_t)sub + 1u)].ts < t;
-        const uint32_t c = (uint32_t)__popcll(group_bits<G>(__ballot(before), group));   // monotone in the lane
-        if (wide) {
-            const int64_t na = (c > 0) ? pivot(c) + 1 : a;
-            const int64_t nb = (c < (uint32_t)G) ? pivot(c + 1u) : b;
-            a = na;
-            b = nb;
-            wide = b - a > G;
+__device__ __forceinline__ int64_t group_cutoff(const TaserRec* __restrict__ rec, const TaserTimeIndex& index,
+                                                int64_t lo, int64_t hi, int64_t t, int group, int sub) {
+    int top = 0;
+    while (top < kTimeIndexLevels && ((hi >> (4 * top)) - (lo >> (4 * top))) > 15) ++top;
+    int64_t at = 0;   // entry of the current level that holds p*
+    for (int L = kTimeIndexLevels; L >= 0; --L) {
+        const bool active = L <= top;
+        if (!__ballot(active)) continue;   // no group of this wave is at this level yet
+        int64_t first = at * 16;
+        int width = 16;
+        if (L == top) {
+            first = lo >> (4 * L);
+            width = (int)((hi >> (4 * L)) - first) + 1;
         }
+        const int64_t len = L == 0 ? index.num_entries : index.len[L - 1];
+        bool before = false;
+        if (active && sub < width) {
+            const int64_t i = first + sub;
+            if (i < len) {
+                int64_t pos = ((i + 1) << (4 * L)) - 1;                  // last position the entry stands for
+                if (pos >= index.num_entries) pos = index.num_entries - 1;
+                if (pos < lo) before = true;
+                else if (pos < hi) before = (L == 0 ? rec[pos].ts : index.level[L - 1][i]) < t;
+            }
+        }
+        const int c = __popcll(group_bits<G>(__ballot(before), group));   // before is monotone in the lane
+        if (active) at = first + c;
     }
-    const int64_t p = a + sub;
-    const bool before = (p < b) && (rec[p].ts < t);
-    return a + __popcll(group_bits<G>(__ballot(before), group)) - lo;
+    // `at` is p*, except past the array's last, partial entry, where it overshoots hi
+    return (at < hi ? at : hi) - lo;
 }
 
 __device__ __forceinline__ void store_slot(int32_t* o_nbr, int32_t* o_eid, int64_t* o_ts,
@@ -68,7 +81,7 @@ constexpr int kThreads = 256;
 // G lanes per root: G >= k, and G >= m for the weighted policy.
 template <int POLICY, int G>
 __global__ __launch_bounds__(kThreads) void sample_hop_kernel(
-    const int64_t* __restrict__ indptr, const TaserRec* __restrict__ rec,
+    const int64_t* __restrict__ indptr, const TaserRec* __restrict__ rec, const TaserTimeIndex index,
     const int32_t* __restrict__ roots, const int64_t* __restrict__ times, int64_t num_roots,
     int32_t num_nodes, int k, uint32_t seed_lo, uint32_t seed_hi, uint32_t hop, int m, const uint32_t* __restrict__ edge_weight,
     int32_t* __restrict__ o_nbr, int32_t* __restrict__ o_eid, int64_t* __restrict__ o_ts,
@@ -88,7 +101,7 @@ __global__ __launch_bounds__(kThreads) void sample_hop_kernel(
             hi = indptr[v + 1];
         }
     }
-    const int64_t cnt = group_cutoff<G>(rec, lo, hi, t, group, sub);   // 0 for dead groups (lo == hi)
+    const int64_t cnt = group_cutoff<G>(rec, index, lo, hi, t, group, sub);   // 0 for dead groups (lo == hi)
     const int64_t out0 = q * k;
     const TaserRec pad = {0, -1, -1};
     int filled = 0;
@@ -208,7 +221,8 @@ constexpr int kMaxTiles = kTileRows * kWave;      // tile sums per root
 // sums, re-reads only the tile it lands in, and takes the picked weight out of the
 // tile's sum, so a draw costs one tile, not the list.
 __global__ __launch_bounds__(kThreads) void sample_hop_inverse_timespan_kernel(
-    const int64_t* __restrict__ indptr, const TaserRec* __restrict__ rec, const int32_t* __restrict__ roots,
+    const int64_t* __restrict__ indptr, const TaserRec* __restrict__ rec, const TaserTimeIndex index,
+    const int32_t* __restrict__ roots,
     const int64_t* __restrict__ times, int64_t num_roots, int32_t num_nodes, int k, uint32_t seed_lo, uint32_t seed_hi,
     uint32_t hop, int32_t* __restrict__ o_nbr, int32_t* __restrict__ o_eid, int64_t* __restrict__ o_ts,
     int32_t* __restrict__ o_count) {
@@ -223,7 +237,7 @@ __global__ __launch_bounds__(kThreads) void sample_hop_inverse_timespan_kernel(
         lo = indptr[v];
         hi = indptr[v + 1];
     }
-    const int64_t cnt = group_cutoff<kWave>(rec, lo, hi, t, 0, lane);
+    const int64_t cnt = group_cutoff<kWave>(rec, index, lo, hi, t, 0, lane);
     const int64_t out0 = q * k;
     const TaserRec pad = {0, -1, -1};
     if (cnt <= k) {   // everything, most recent first
@@ -334,8 +348,8 @@ void launch_hop_g(const taser_tcsr* g, const int32_t* roots, const int64_t* time
                   hipStream_t stream) {
     constexpr int roots_per_block = (kThreads / kWave) * (kWave / G);
     const unsigned grid = (unsigned)((n + roots_per_block - 1) / roots_per_block);
-    hipLaunchKernelGGL((sample_hop_kernel<POLICY, G>), dim3(grid), dim3(kThreads), 0, stream, g->indptr, g->rec, roots,
-                       times, n, g->num_nodes, k, (uint32_t)seed, (uint32_t)(seed >> 32), hop, m, edge_weight, o.nbr,
+    hipLaunchKernelGGL((sample_hop_kernel<POLICY, G>), dim3(grid), dim3(kThreads), 0, stream, g->indptr, g->rec, g->time_index,
+                       roots, times, n, g->num_nodes, k, (uint32_t)seed, (uint32_t)(seed >> 32), hop, m, edge_weight, o.nbr,
                        o.eid, o.ts, o.count);
 }
 
@@ -388,7 +402,7 @@ extern "C" int taser_sample_temporal(const taser_tcsr* g, const int32_t* roots, 
                 TaserProfileSpan span(stream, "sample_hop_inverse_timespan");
                 const unsigned grid = (unsigned)((n + kThreads / kWave - 1) / (kThreads / kWave));
                 hipLaunchKernelGGL(sample_hop_inverse_timespan_kernel, dim3(grid), dim3(kThreads), 0, stream, g->indptr, g->rec,
-                                   cur_roots, cur_times, n, g->num_nodes, k, (uint32_t)seed, (uint32_t)(seed >> 32),
+                                   g->time_index, cur_roots, cur_times, n, g->num_nodes, k, (uint32_t)seed, (uint32_t)(seed >> 32),
                                    (uint32_t)h, out[h].nbr, out[h].eid, out[h].ts, out[h].count);
                 break;
             }

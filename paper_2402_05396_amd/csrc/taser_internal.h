@@ -29,11 +29,26 @@ struct __attribute__((aligned(16))) TaserRec {
     int32_t eid;
 };
 
+// Search index over the timestamps of the whole record array (all lists back to
+// back): level l = 1..kTimeIndexLevels holds, for every run of 16^l consecutive
+// records, the timestamp of the run's last record (of the array's last record for
+// the final, partial run). A search for a query time inside one node's list reads
+// one 128-byte line of 16 neighboring entries per level instead of 16 scattered
+// records; the upper levels are small enough to stay in L2.
+constexpr int kTimeIndexLevels = 7;   // 16^7 = 2^28: at the top a list of < 2^31 records spans < 16 entries
+struct TaserTimeIndex {
+    const int64_t* level[kTimeIndexLevels];   // level[l - 1]: device int64[len[l - 1]]
+    int64_t len[kTimeIndexLevels];            // ceil(num_entries / 16^l)
+    int64_t num_entries;
+};
+
 struct taser_tcsr {
     int64_t num_entries;
     int32_t num_nodes;
     int64_t* indptr;   // device int64[num_nodes + 1]
     TaserRec* rec;     // device TaserRec[num_entries], T-CSR order
+    int64_t* time_index_storage;   // one device allocation behind time_index.level[*]
+    TaserTimeIndex time_index;
 };
 
 static constexpr int kWave = 64;

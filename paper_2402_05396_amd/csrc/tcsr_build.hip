@@ -217,7 +217,25 @@ struct DevBuf {
 
 inline unsigned blocks_for(int64_t n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
 
+// Level 1 of the search index straight from the records, every further level from the one below.
+__global__ __launch_bounds__(kThreads) void time_index_first_kernel(const TaserRec* __restrict__ rec, int64_t n,
+                                                                    int64_t* __restrict__ out, int64_t len) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= len) return;
+    const int64_t last = 16 * (i + 1) - 1;
+    out[i] = rec[last < n ? last : n - 1].ts;
+}
+
+__global__ __launch_bounds__(kThreads) void time_index_next_kernel(const int64_t* __restrict__ below, int64_t below_len,
+                                                                   int64_t* __restrict__ out, int64_t len) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= len) return;
+    const int64_t last = 16 * (i + 1) - 1;
+    out[i] = below[last < below_len ? last : below_len - 1];
+}
+
 }  // namespace
+
 
 extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const int64_t* ts,
                                 const int32_t* eid, int64_t num_entries, int32_t num_nodes,
@@ -327,6 +345,28 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
         hipLaunchKernelGGL(indptr_kernel, dim3(blocks_for(n + 1, kThreads)), dim3(kThreads), 0, stream,
                            key_a.as<int32_t>(), n, num_nodes, indptr.as<int64_t>());
     }
+    // ---- search index over the sorted timestamps
+    TaserTimeIndex index = {};
+    index.num_entries = n;
+    int64_t index_total = 0, level_at[kTimeIndexLevels];
+    for (int l = 0; l < kTimeIndexLevels; ++l) {
+        const int64_t below = l == 0 ? n : index.len[l - 1];
+        index.len[l] = (below + 15) / 16;
+        level_at[l] = index_total;
+        index_total += index.len[l];
+    }
+    DevBuf index_storage;
+    TASER_HIP_TRY(index_storage.alloc((size_t)(index_total > 0 ? index_total : 1) * sizeof(int64_t)));
+    for (int l = 0; l < kTimeIndexLevels; ++l) index.level[l] = index_storage.as<int64_t>() + level_at[l];
+    if (n > 0) {
+        TaserProfileSpan span(stream, "tcsr_time_index");
+        hipLaunchKernelGGL(time_index_first_kernel, dim3(blocks_for(index.len[0], kThreads)), dim3(kThreads), 0, stream,
+                           rec_a.as<TaserRec>(), n, index_storage.as<int64_t>() + level_at[0], index.len[0]);
+        for (int l = 1; l < kTimeIndexLevels; ++l)
+            hipLaunchKernelGGL(time_index_next_kernel, dim3(blocks_for(index.len[l], kThreads)), dim3(kThreads), 0, stream,
+                               index.level[l - 1], index.len[l - 1], index_storage.as<int64_t>() + level_at[l],
+                               index.len[l]);
+    }
     TASER_HIP_TRY(hipGetLastError());
     TASER_HIP_TRY(hipStreamSynchronize(stream));
 
@@ -336,6 +376,8 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
     g->num_nodes = num_nodes;
     g->indptr = indptr.release<int64_t>();
     g->rec = rec_a.release<TaserRec>();
+    g->time_index_storage = index_storage.release<int64_t>();
+    g->time_index = index;
     *out = g;
     return TASER_OK;
 }
@@ -367,5 +409,6 @@ extern "C" void taser_tcsr_free(taser_tcsr* g) {
     if (!g) return;
     (void)hipFree(g->indptr);
     (void)hipFree(g->rec);
+    (void)hipFree(g->time_index_storage);
     delete g;
 }
