@@ -25,8 +25,8 @@ EDGE_PITCH_ELEMS = {186: 192}   # rows padded to whole 128-byte lines where the 
 # HBM traffic per launch of the dominant kernel measured offline with
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/c5_gdelt_shaped_hbm_traffic_pmc.txt: (2 x 335 975.7 + 2 148 923.3) KiB per launch
-    ("C5-gdelt-shaped", "cache_gather_rows"): 2888565000,
+    # profiles/c5_gdelt_shaped_hbm_traffic_pmc.txt: (2 x 335 901.5 + 2 148 915.1) KiB per launch
+    ("C5-gdelt-shaped", "cache_gather_rows"): 2888415000,
 }
 
 
@@ -41,7 +41,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5, choices=[3, 4, 5])
     ap.add_argument("--edges", type=int, default=None, help="override the event count (smaller = not the named workload)")
-    ap.add_argument("--schedule", default="pipeline", choices=["serial", "overlap", "pipeline"])
+    ap.add_argument("--schedule", default="pipeline", choices=["serial", "overlap", "pipeline", "pipeline_node_first"])
     ap.add_argument("--stage-blocks", type=int, default=16, help="width of the PCIe staging copy when it runs beside other kernels")
     ap.add_argument("--policy", default=None, choices=["recent", "uniform", "weighted", "inverse_timespan"],
                     help="override the workload's selection policy (then it is not the named workload)")
@@ -163,6 +163,14 @@ def main():
             side.wait_event(ev_sampled[s])
             T.cache_prefetch(caches[s], b["ids"], hit_miss=hit_miss, stream=side)
             ev_staged[s].record(side)
+            if args.schedule == "pipeline_node_first":
+                if pending is not None:
+                    pb, ps = pending
+                    main.wait_event(ev_staged[ps])
+                    T.cache_gather(caches[ps], pb["ids"], out=node_out[ps], stream=main)
+                pending = (b, s)
+                T.gather_features(edge_table, b["eids"], out=edge_out[s], stream=main)
+                continue
             T.gather_features(edge_table, b["eids"], out=edge_out[s], stream=main)
             if args.schedule == "pipeline":
                 if pending is not None:
