@@ -41,10 +41,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5, choices=[3, 4, 5])
     ap.add_argument("--edges", type=int, default=None, help="override the event count (smaller = not the named workload)")
-    ap.add_argument("--schedule", default="pipeline", choices=["serial", "overlap", "pipeline", "pipeline_node_first"])
+    ap.add_argument("--schedule", default="pipeline", choices=["serial", "overlap", "pipeline", "pipeline_node_first", "pipeline3"])
     ap.add_argument("--stage-blocks", type=int, default=16, help="width of the PCIe staging copy when it runs beside other kernels")
     ap.add_argument("--policy", default=None, choices=["recent", "uniform", "weighted", "inverse_timespan"],
                     help="override the workload's selection policy (then it is not the named workload)")
+    ap.add_argument("--cache-ratio", type=float, default=None,
+                    help="override the share of node rows resident in the device cache (then it is not the named workload)")
     ap.add_argument("--cpu-roots", type=int, default=6000, help="roots of batch 0 the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -98,7 +100,7 @@ def main():
     cache = None
     if w.node_feat is not None:
         node_host = torch.from_numpy(w.node_feat).pin_memory()
-        cap = int(w.cache_ratio * w.num_nodes)
+        cap = int((w.cache_ratio if args.cache_ratio is None else args.cache_ratio) * w.num_nodes)
         hot = torch.from_numpy(np.ascontiguousarray(w.notes["hot_order"][:cap]))
         cache = T.cache_init(node_host, cap, hot, staging_rows=w.num_nodes - cap)
     torch.cuda.synchronize()
@@ -140,8 +142,12 @@ def main():
     ev_sampled = [torch.cuda.Event() for _ in range(n_buf)]
     ev_staged = [torch.cuda.Event() for _ in range(n_buf)]
 
-    def sample(b):
-        T.sample_temporal(g, b["roots"], b["times"], k, hops, policy, 42, w.m, weight, out=b["out"], stream=main)
+    samp = torch.cuda.Stream()                       # pipeline3 only: the sampler's own stream
+    ev_consumed = [None] * len(batches)              # pipeline3: a batch's buffers were read for the last time
+
+    def sample(b, stream=None):
+        T.sample_temporal(g, b["roots"], b["times"], k, hops, policy, 42, w.m, weight, out=b["out"],
+                          stream=main if stream is None else stream)
 
     def run(first, count):
         """`count` passes of the whole path over consecutive batches.
@@ -153,6 +159,27 @@ def main():
         pending = None
         for i in range(count):
             b, s = batches[(first + i) % len(batches)], i % n_buf
+            if args.schedule == "pipeline3" and cache is not None:
+                # pipeline3: as pipeline, and the sampler (latency-bound, little bandwidth) runs on a
+                # stream of its own beside the gathers of the batches before it.
+                bi = (first + i) % len(batches)
+                if ev_consumed[bi] is not None:
+                    samp.wait_event(ev_consumed[bi])
+                sample(b, samp)
+                ev_sampled[s].record(samp)
+                main.wait_event(ev_sampled[s])
+                side.wait_event(ev_sampled[s])
+                T.cache_prefetch(caches[s], b["ids"], hit_miss=hit_miss, stream=side)
+                ev_staged[s].record(side)
+                T.gather_features(edge_table, b["eids"], out=edge_out[s], stream=main)
+                if pending is not None:
+                    pb, ps, pbi = pending
+                    main.wait_event(ev_staged[ps])
+                    T.cache_gather(caches[ps], pb["ids"], out=node_out[ps], stream=main)
+                    ev_consumed[pbi] = torch.cuda.Event()
+                    ev_consumed[pbi].record(main)
+                pending = (b, s, bi)
+                continue
             sample(b)
             if cache is None or args.schedule == "serial":
                 T.gather_features(edge_table, b["eids"], out=edge_out[s], stream=main)
@@ -182,9 +209,12 @@ def main():
                 main.wait_event(ev_staged[s])
                 T.cache_gather(caches[s], b["ids"], out=node_out[s], stream=main)
         if pending is not None:
-            pb, ps = pending
+            pb, ps = pending[:2]
             main.wait_event(ev_staged[ps])
             T.cache_gather(caches[ps], pb["ids"], out=node_out[ps], stream=main)
+            if len(pending) == 3:
+                ev_consumed[pending[2]] = torch.cuda.Event()
+                ev_consumed[pending[2]].record(main)
 
     # Warm-up, with every library kernel bracketed by events: this names the dominant
     # HBM-bound kernel (the longest of the two gathers; the staging kernel is bound by PCIe
@@ -348,7 +378,10 @@ def main():
                    "events": w.num_edges, "nodes": w.num_nodes, "roots_per_batch": R, "fanout": [k] * hops,
                    "policy": ["recent", "uniform", "weighted", "inverse_timespan"][policy] + ("" if args.policy is None else " (override)"), "edge_row_bytes": edge_rb,
                    "node_row_bytes": node_rb, "distinct_batches": len(batches),
-                   "cache_rows": 0 if cache is None else cache.capacity, "schedule": args.schedule},
+                   "cache_rows": (0 if cache is None else cache.capacity) if args.cache_ratio is None
+                   else f"{cache.capacity} (override)", "schedule": args.schedule},
+        "sampler_neighbors_per_s": round(neighbors / args.steps / (sum(ms for n, (c, ms) in kernels.items()
+                                                                       if n.startswith("sample_hop")) / args.steps * 1e-3), 1),
         "gather_GBps": round(gather_gbps, 1), "gather_frac_of_hbm_peak": round(gather_gbps / HBM_PEAK_GBPS, 4),
         "gather_bytes_per_step": gather_bytes_per_step, "neighbors_per_step": neighbors / args.steps,
         "cache_hit_rate": None if cache is None or sum(hm) == 0 else round(hm[0] / sum(hm), 4),

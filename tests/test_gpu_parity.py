@@ -80,11 +80,11 @@ def test_c2_one_hop_recent_and_uniform():
     assert_tcsr_equal(g, g_ref)
     table = dev(w.edge_feat)
     assert len(w.batches) == 267 and w.batches[-1][0].shape[0] == 1200
-    for b in (0, 1, 2, 50, 133, 200, 265, 266):        # cold start ... ragged last batch
-        roots, times = w.batches[b]
+    for b, (roots, times) in enumerate(w.batches):     # the whole chronological pass, cold start to the ragged last batch
         for policy in w.policies:
             got, want = run_both(g, g_ref, roots, times, w.k, 1, policy, seed=42)
-            check_gather(w.edge_feat, table, got[0]["eid"], want[0]["eid"])
+            if b in (0, 1, 2, 50, 133, 200, 265, 266):
+                check_gather(w.edge_feat, table, got[0]["eid"], want[0]["eid"])
 
 
 def test_c3_two_hop_uniform_fp16():
