@@ -41,10 +41,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5, choices=[3, 4, 5])
     ap.add_argument("--edges", type=int, default=None, help="override the event count (smaller = not the named workload)")
-    ap.add_argument("--schedule", default="pipeline", choices=["serial", "overlap", "pipeline", "pipeline_node_first", "pipeline3"])
-    ap.add_argument("--stage-blocks", type=int, default=16, help="width of the PCIe staging copy when it runs beside other kernels")
+    ap.add_argument("--schedule", default="pipeline_node_first",
+                    choices=["serial", "overlap", "pipeline", "pipeline_node_first", "pipeline3"])
+    ap.add_argument("--stage-blocks", type=int, default=32, help="width of the PCIe staging copy when it runs beside other kernels")
     ap.add_argument("--policy", default=None, choices=["recent", "uniform", "weighted", "inverse_timespan"],
                     help="override the workload's selection policy (then it is not the named workload)")
+    ap.add_argument("--no-refresh", action="store_true", help="do not re-write the gather's working set before the node gather")
     ap.add_argument("--cache-ratio", type=float, default=None,
                     help="override the share of node rows resident in the device cache (then it is not the named workload)")
     ap.add_argument("--cpu-roots", type=int, default=6000, help="roots of batch 0 the CPU oracle is timed on (0 = skip)")
@@ -135,7 +137,7 @@ def main():
         caches.append(T.cache_init(node_host, cap, hot, staging_rows=w.num_nodes - cap))
         if args.schedule != "serial":
             for c in caches:
-                T.cache_tune(c, stage_blocks=args.stage_blocks, refresh_before_gather=True)
+                T.cache_tune(c, stage_blocks=args.stage_blocks, refresh_before_gather=not args.no_refresh)
     hit_miss = torch.zeros(2, dtype=torch.int64, device=dev)
     main = torch.cuda.current_stream()
     side = torch.cuda.Stream()                       # same (default) priority as the main stream
@@ -155,7 +157,9 @@ def main():
         overlap:  per batch, the PCIe staging of missed node rows runs on a side stream beside
                   the edge gather.
         pipeline: the staging of batch i also runs beside the sampling and edge gather of batch
-                  i+1; the node gather of batch i is issued one batch late (two buffer sets)."""
+                  i+1; the node gather of batch i is issued one batch late (two buffer sets).
+        pipeline_node_first (default): the same, with the late node gather issued before the
+                  edge gather of the current batch."""
         pending = None
         for i in range(count):
             b, s = batches[(first + i) % len(batches)], i % n_buf

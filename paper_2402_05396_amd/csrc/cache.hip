@@ -10,14 +10,14 @@
 // access a hot non-resident row is otherwise re-read hundreds of times per
 // batch over a bus 100x slower than HBM).
 //
-// A lookup is four launches (1-3 = taser_cache_prefetch, 4 = taser_cache_gather;
+// A lookup is three kernels (1-2 = taser_cache_prefetch, 3 = taser_cache_gather;
 // split so that a caller can run the bus-bound part beside other work):
-//   1. clear the per-call miss table;
-//   2. classify: every request probes the resident hash; a miss claims a slot
+//   1. classify: every request probes the resident hash; a miss claims a slot
 //      of the miss table (compare-and-swap on the id, the slot index doubles as
 //      the staging row) — the outcome per request is written to `loc`;
-//   3. stage: one wave per claimed slot copies that row host -> staging;
-//   4. gather: the dense output is written from cache rows / staged rows /
+//   2. stage: one wave per claimed slot copies that row host -> staging and
+//      empties the slot, so the miss table is clear again for the next call;
+//   3. gather: the dense output is written from cache rows / staged rows /
 //      zero rows, or straight from host memory for requests that found the
 //      miss table full.
 // Which rows are resident only changes where bytes come from, never the bytes.
@@ -38,6 +38,7 @@ constexpr int32_t kLocHost = INT32_MIN;            // read the host row directly
 constexpr int kMaxMissProbes = 128;
 constexpr int kTallySlots = 1024;                 // per-block LDS table of the access counting
 constexpr uint32_t kTagCache = 0x43414348u;        // hop tag of the residency shuffle
+constexpr int kClassifyBlocks = 2048;             // grid-stride: 8 blocks per compute unit
 
 __host__ __device__ inline uint32_t hash_id(int32_t id, uint32_t mask) {
     uint32_t h = (uint32_t)id * 0x9E3779B1u;
@@ -73,6 +74,7 @@ struct taser_cache {
     int32_t* resident_dev;             // device copy of the same
     uint32_t* access_count;            // device [rows] or null: requests per row since the last epoch end
     bool counting;
+    uint32_t* block_tally;             // device [2 * kClassifyBlocks]: hits, misses of every classify block
 };
 
 namespace {
@@ -82,13 +84,13 @@ __global__ __launch_bounds__(kThreads) void fill_kernel(int32_t* a, uint32_t n, 
     if (i < n) a[i] = v;
 }
 
-// Grid-stride over the requests; hit/miss counts are summed per block and added
-// to the caller's counters with one atomic pair per block (a pair per wave
-// would put tens of thousands of atomics on one address).
+// Grid-stride over the requests; hit/miss counts are summed per block and left in
+// block_tally for tally_kernel (even one atomic pair per block on the caller's two
+// counters, thousands on one address, took longer than the classification itself).
 __global__ __launch_bounds__(kThreads) void classify_kernel(
     const int32_t* __restrict__ ids, int64_t n, int64_t rows, const int32_t* __restrict__ hash_key,
     const int32_t* __restrict__ hash_slot, uint32_t hash_mask, int32_t* miss_key, uint32_t miss_size,
-    int32_t* __restrict__ loc, unsigned long long* hit_miss, uint32_t* access_count) {
+    int32_t* __restrict__ loc, uint32_t* __restrict__ block_tally, uint32_t* access_count) {
     __shared__ uint32_t block_hits[kThreads / kWave], block_misses[kThreads / kWave];
     // Access counting: a block first sums its own requests per id in a small LDS
     // hash table and adds each distinct id to the global counter once, so a row
@@ -153,7 +155,7 @@ __global__ __launch_bounds__(kThreads) void classify_kernel(
         for (int s = threadIdx.x; s < kTallySlots; s += kThreads)
             if (tally_key[s] != kEmpty) atomicAdd(&access_count[tally_key[s]], tally_count[s]);
     }
-    if (!hit_miss) return;
+    if (!block_tally) return;
     for (int d = kWave / 2; d > 0; d >>= 1) {
         hits += __shfl_down(hits, d, kWave);
         misses += __shfl_down(misses, d, kWave);
@@ -170,8 +172,38 @@ __global__ __launch_bounds__(kThreads) void classify_kernel(
             h += block_hits[w];
             m += block_misses[w];
         }
-        if (h) atomicAdd(&hit_miss[0], (unsigned long long)h);
-        if (m) atomicAdd(&hit_miss[1], (unsigned long long)m);
+        block_tally[2 * blockIdx.x] = h;
+        block_tally[2 * blockIdx.x + 1] = m;
+    }
+}
+
+// One block: adds the per-block counts of the classify launch before it to the
+// caller's two counters.
+__global__ __launch_bounds__(kThreads) void tally_kernel(const uint32_t* __restrict__ block_tally, int blocks,
+                                                         unsigned long long* hit_miss) {
+    __shared__ unsigned long long part[2][kThreads / kWave];
+    unsigned long long h = 0, m = 0;
+    for (int b = threadIdx.x; b < blocks; b += kThreads) {
+        h += block_tally[2 * b];
+        m += block_tally[2 * b + 1];
+    }
+    for (int d = kWave / 2; d > 0; d >>= 1) {
+        h += __shfl_down(h, d, kWave);
+        m += __shfl_down(m, d, kWave);
+    }
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+        part[0][threadIdx.x >> 6] = h;
+        part[1][threadIdx.x >> 6] = m;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        h = m = 0;
+        for (int w = 0; w < kThreads / kWave; ++w) {
+            h += part[0][w];
+            m += part[1][w];
+        }
+        if (h) atomicAdd(&hit_miss[0], h);
+        if (m) atomicAdd(&hit_miss[1], m);
     }
 }
 
@@ -181,7 +213,7 @@ __global__ __launch_bounds__(kThreads) void classify_kernel(
 // a wave reads 64 table slots at a time and walks the claimed ones.
 constexpr int kStageBlocks = 64;
 
-__global__ __launch_bounds__(kThreads) void stage_kernel(const int32_t* __restrict__ miss_key, uint32_t miss_size,
+__global__ __launch_bounds__(kThreads) void stage_kernel(int32_t* __restrict__ miss_key, uint32_t miss_size,
                                                          const uint8_t* __restrict__ host_rows, int64_t pitch_bytes,
                                                          uint32_t row_dwords, uint8_t* __restrict__ stage_rows,
                                                          int32_t dev_pitch) {
@@ -192,6 +224,7 @@ __global__ __launch_bounds__(kThreads) void stage_kernel(const int32_t* __restri
     const uint32_t chunks = row_dwords / 4u, tail = row_dwords & 3u;
     for (uint32_t base = wave * kWave; base < miss_size; base += num_waves * kWave) {   // miss_size % 64 == 0
         const int32_t key = miss_key[base + lane];
+        if (key >= 0) miss_key[base + lane] = kEmpty;   // the table is empty again for the next call's claims
         uint64_t claimed = __ballot(key >= 0);
         while (claimed) {
             const int l = __ffsll((long long)claimed) - 1;
@@ -339,7 +372,7 @@ uint32_t pow2_at_least(uint64_t x) {
 void destroy(taser_cache* c) {
     if (!c) return;
     void* const owned[] = {c->cache_rows, c->hash_key, c->hash_slot, c->stage_rows, c->miss_key,
-                           c->loc, c->resident_dev, c->access_count};
+                           c->loc, c->resident_dev, c->access_count, c->block_tally};
     int at = 0;
     for (void* p : owned) {
         const hipError_t e = p ? hipFree(p) : hipSuccess;
@@ -465,9 +498,12 @@ extern "C" int taser_cache_init(const void* host_table, int64_t rows, int32_t ro
     CACHE_TRY(hipMalloc((void**)&c->hash_key, (size_t)hash_size * sizeof(int32_t)));
     CACHE_TRY(hipMalloc((void**)&c->hash_slot, (size_t)hash_size * sizeof(int32_t)));
     CACHE_TRY(hipMalloc((void**)&c->resident_dev, (size_t)(capacity_rows > 0 ? capacity_rows : 1) * sizeof(int32_t)));
+    CACHE_TRY(hipMalloc((void**)&c->block_tally, (size_t)2 * kClassifyBlocks * sizeof(uint32_t)));
     if (c->miss_size) {
         CACHE_TRY(hipMalloc((void**)&c->stage_rows, (size_t)c->miss_size * c->dev_pitch));
         CACHE_TRY(hipMalloc((void**)&c->miss_key, (size_t)c->miss_size * sizeof(int32_t)));
+        hipLaunchKernelGGL(fill_kernel, dim3((c->miss_size + kThreads - 1) / kThreads), dim3(kThreads), 0, stream,
+                           c->miss_key, c->miss_size, kEmpty);
     }
 #undef CACHE_TRY
     const int rc = install_residents(c, stream);
@@ -496,17 +532,16 @@ extern "C" int taser_cache_prefetch(taser_cache* c, const int32_t* ids, int64_t 
         c->loc_capacity = n;
     }
     int64_t blocks = (n + kThreads - 1) / kThreads;
-    if (blocks > 2048) blocks = 2048;   // grid-stride: 8 blocks per compute unit
-    if (c->miss_size) {
-        TaserProfileSpan span(stream, "cache_clear_miss_table");
-        hipLaunchKernelGGL(fill_kernel, dim3((c->miss_size + kThreads - 1) / kThreads), dim3(kThreads), 0, stream,
-                           c->miss_key, c->miss_size, kEmpty);
-    }
+    if (blocks > kClassifyBlocks) blocks = kClassifyBlocks;
+    // miss_key is all-empty here: cache_init cleared it and every stage_kernel clears what it consumed
     {
         TaserProfileSpan span(stream, "cache_classify");
         hipLaunchKernelGGL(classify_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, ids, n, c->rows,
                            c->hash_key, c->hash_slot, c->hash_mask, c->miss_key, c->miss_size, c->loc,
-                           reinterpret_cast<unsigned long long*>(hit_miss), c->counting ? c->access_count : nullptr);
+                           hit_miss ? c->block_tally : nullptr, c->counting ? c->access_count : nullptr);
+        if (hit_miss)
+            hipLaunchKernelGGL(tally_kernel, dim3(1), dim3(kThreads), 0, stream, c->block_tally, (int)blocks,
+                               reinterpret_cast<unsigned long long*>(hit_miss));
     }
     if (c->miss_size) {
         TaserProfileSpan span(stream, "cache_stage_misses");
