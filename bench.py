@@ -42,7 +42,7 @@ def main():
     ap.add_argument("--config", type=int, default=5, choices=[3, 4, 5])
     ap.add_argument("--edges", type=int, default=None, help="override the event count (smaller = not the named workload)")
     ap.add_argument("--schedule", default="pipeline_node_first",
-                    choices=["serial", "overlap", "pipeline", "pipeline_node_first", "pipeline3"])
+                    choices=["serial", "overlap", "pipeline", "pipeline_node_first"])
     ap.add_argument("--stage-blocks", type=int, default=32, help="width of the PCIe staging copy when it runs beside other kernels")
     ap.add_argument("--policy", default=None, choices=["recent", "uniform", "weighted", "inverse_timespan"],
                     help="override the workload's selection policy (then it is not the named workload)")
@@ -144,12 +144,8 @@ def main():
     ev_sampled = [torch.cuda.Event() for _ in range(n_buf)]
     ev_staged = [torch.cuda.Event() for _ in range(n_buf)]
 
-    samp = torch.cuda.Stream()                       # pipeline3 only: the sampler's own stream
-    ev_consumed = [None] * len(batches)              # pipeline3: a batch's buffers were read for the last time
-
-    def sample(b, stream=None):
-        T.sample_temporal(g, b["roots"], b["times"], k, hops, policy, 42, w.m, weight, out=b["out"],
-                          stream=main if stream is None else stream)
+    def sample(b):
+        T.sample_temporal(g, b["roots"], b["times"], k, hops, policy, 42, w.m, weight, out=b["out"], stream=main)
 
     def run(first, count):
         """`count` passes of the whole path over consecutive batches.
@@ -163,27 +159,6 @@ def main():
         pending = None
         for i in range(count):
             b, s = batches[(first + i) % len(batches)], i % n_buf
-            if args.schedule == "pipeline3" and cache is not None:
-                # pipeline3: as pipeline, and the sampler (latency-bound, little bandwidth) runs on a
-                # stream of its own beside the gathers of the batches before it.
-                bi = (first + i) % len(batches)
-                if ev_consumed[bi] is not None:
-                    samp.wait_event(ev_consumed[bi])
-                sample(b, samp)
-                ev_sampled[s].record(samp)
-                main.wait_event(ev_sampled[s])
-                side.wait_event(ev_sampled[s])
-                T.cache_prefetch(caches[s], b["ids"], hit_miss=hit_miss, stream=side)
-                ev_staged[s].record(side)
-                T.gather_features(edge_table, b["eids"], out=edge_out[s], stream=main)
-                if pending is not None:
-                    pb, ps, pbi = pending
-                    main.wait_event(ev_staged[ps])
-                    T.cache_gather(caches[ps], pb["ids"], out=node_out[ps], stream=main)
-                    ev_consumed[pbi] = torch.cuda.Event()
-                    ev_consumed[pbi].record(main)
-                pending = (b, s, bi)
-                continue
             sample(b)
             if cache is None or args.schedule == "serial":
                 T.gather_features(edge_table, b["eids"], out=edge_out[s], stream=main)
@@ -213,12 +188,9 @@ def main():
                 main.wait_event(ev_staged[s])
                 T.cache_gather(caches[s], b["ids"], out=node_out[s], stream=main)
         if pending is not None:
-            pb, ps = pending[:2]
+            pb, ps = pending
             main.wait_event(ev_staged[ps])
             T.cache_gather(caches[ps], pb["ids"], out=node_out[ps], stream=main)
-            if len(pending) == 3:
-                ev_consumed[pending[2]] = torch.cuda.Event()
-                ev_consumed[pending[2]].record(main)
 
     # Warm-up, with every library kernel bracketed by events: this names the dominant
     # HBM-bound kernel (the longest of the two gathers; the staging kernel is bound by PCIe
