@@ -78,6 +78,10 @@ def main():
 
     # ------------------------------------------------------------------ resident inputs
     d_src, d_dst, d_ts, d_eid = (torch.from_numpy(x).to(dev) for x in (w.src, w.dst, w.ts, w.eid))
+    # a tiny build first: the first launch of a kernel also loads its code object, which would
+    # otherwise be counted in the first timed kernel (about 0.6 ms)
+    T.tcsr_free(T.tcsr_build(d_src[:4096].contiguous(), d_dst[:4096].contiguous(), d_ts[:4096].contiguous(),
+                             d_eid[:4096].contiguous(), w.num_nodes))
     torch.cuda.synchronize()
     T.profile_begin()
     t0 = time.time()
@@ -254,6 +258,33 @@ def main():
             roofline["traffic_GBps"] = round(t_gbps, 1)               # measured HBM-side bytes / measured time
             roofline["traffic_frac"] = round(t_gbps / HBM_PEAK_GBPS, 4)
 
+    # Every row of the path against the roofline that bounds it (per-kernel times of the second pass;
+    # algorithmic bytes: what the step must move, not transactions or line padding).
+    def hbm_row(alg, ms, note=None):
+        r = {"bound": "hbm", "algorithmic_bytes": int(alg), "ms": round(ms, 4),
+             "achieved_GBps": round(alg / (ms * 1e-3) / 1e9, 1), "frac_of_hbm_peak": round(alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        if note:
+            r["note"] = note
+        return r
+    n_entries = int(w.src.shape[0])
+    sample_ms = sum(ms for n, (c, ms) in kernels.items() if n.startswith("sample_hop")) / args.steps
+    roots_per_step = R + sum(n_slots[:-1])
+    rows_report = {
+        "a1_tcsr_build": hbm_row(n_entries * (20 + 16) + (w.num_nodes + 1) * 8, build_dev_ms,
+                                 "once per graph; bytes = 20 in + 16 out per entry; a multi-pass sort moves more"),
+        "a2_a6_sampler": dict(hbm_row(roots_per_step * 20 + neighbors / args.steps * 32 + roots_per_step * 56, sample_ms,
+                                      "bound by dependent-read latency, not bytes: per root 16 B of list bounds + 4 B count + "
+                                      "about 7 index/record probes of 8 B; per kept neighbor 16 B read + 16 B written"),
+                              neighbors_per_s=round(neighbors / args.steps / (sample_ms * 1e-3), 1)),
+        "a7_edge_gather": hbm_row(edge_bytes, per_kernel["gather_rows"]["avg_ms"]),
+    }
+    if cache is not None:
+        lookup_ms = sum(per_kernel[n]["avg_ms"] for n in ("cache_classify", "cache_refresh_working_set", "cache_gather_rows")
+                        if n in per_kernel)
+        rows_report["a8_node_gather_through_cache"] = hbm_row(
+            node_bytes, lookup_ms, "classify + working-set re-write + gather on the HBM side; the staging of missed rows "
+            f"({per_kernel['cache_stage_misses']['avg_ms']:.3f} ms, bus-bound) runs beside it on the side stream")
+
     # ------------------------------------------------------------------ cache maintenance (outside the timed region)
     # Cost of the access counters of Alg. 3 inside the classify kernel, and of one epoch-end
     # top-k + overlap test (no replacement: the residents already are the hottest rows).
@@ -367,7 +398,7 @@ def main():
         "kernels": {n: {"launches": v["launches"], "avg_ms": round(v["avg_ms"], 4)} for n, v in per_kernel.items()},
         "kernels_note": "per-kernel times from a second pass of the same steps with every kernel bracketed by events; "
                         "the roofline kernel's time is from the timed region itself",
-        "cache_maintenance": maintenance, "further_rows": further, "roofline": roofline, "cpu_baseline": cpu,
+        "cache_maintenance": maintenance, "further_rows": further, "rows": rows_report, "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(result), flush=True)
 

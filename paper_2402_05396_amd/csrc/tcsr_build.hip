@@ -46,27 +46,58 @@ __device__ __forceinline__ int64_t item_index(int64_t tile0, int wave, int r, in
     return tile0 + (int64_t)wave * (kWave * kItems) + r * kWave + lane;
 }
 
-// info[0] != 0: a node id outside [0, num_nodes); info[1] != 0: timestamps not
-// non-decreasing in input order; info[2] / info[3]: OR / AND of the biased
-// timestamps (bytes in which they agree need no sorting pass).
-__global__ __launch_bounds__(kThreads) void inspect_kernel(const int32_t* __restrict__ src,
-                                                           const int64_t* __restrict__ ts, int64_t n,
-                                                           int32_t num_nodes, unsigned long long* info) {
+// Packs the input columns into the 16-byte records + node key the sort moves, and
+// inspects them on the way. Per block, partial[4 * block + ...]: [0] != 0: a node id
+// outside [0, num_nodes); [1] != 0: timestamps not non-decreasing in input order;
+// [2] / [3]: OR / AND of the biased timestamps (bytes in which they agree need no
+// sorting pass). fold_info_kernel combines the per-block words (atomics from every
+// block onto four shared words took longer than reading the input).
+__global__ __launch_bounds__(kThreads) void pack_inspect_kernel(const int32_t* __restrict__ src,
+                                                                const int32_t* __restrict__ dst,
+                                                                const int64_t* __restrict__ ts,
+                                                                const int32_t* __restrict__ eid, int64_t n,
+                                                                int32_t num_nodes, TaserRec* __restrict__ rec,
+                                                                int32_t* __restrict__ key,
+                                                                unsigned long long* __restrict__ partial) {
     unsigned long long any_or = 0, all_and = ~0ull;
     int bad = 0, unsorted = 0;
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kThreads) {
-        const int32_t s = src[i];
-        bad |= (s < 0 || s >= num_nodes);
-        const int64_t t = ts[i];
-        if (i + 1 < n) unsorted |= (ts[i + 1] < t);
-        any_or |= biased(t);
-        all_and &= biased(t);
+    constexpr int kPer = 4;   // entries per thread and round: their loads are issued together
+    // a block packs one contiguous tile of kTile entries
+    const int64_t tile0 = (int64_t)blockIdx.x * kTile;
+    for (int round = 0; round < kItems / kPer; ++round) {
+        const int64_t i0 = tile0 + (int64_t)round * (kPer * kThreads) + threadIdx.x;
+        int32_t s[kPer], dn[kPer], e[kPer];
+        int64_t t[kPer], t_next[kPer];
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int64_t i = i0 + u * kThreads;
+            const int64_t at = i < n ? i : n - 1;            // clamped: every load stays in bounds
+            s[u] = src[at];
+            dn[u] = dst[at];
+            t[u] = ts[at];
+            t_next[u] = ts[at + 1 < n ? at + 1 : at];
+            e[u] = eid ? eid[at] : (int32_t)at;
+        }
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int64_t i = i0 + u * kThreads;
+            if (i >= n) continue;
+            bad |= (s[u] < 0 || s[u] >= num_nodes);
+            unsorted |= (t_next[u] < t[u]);
+            any_or |= biased(t[u]);
+            all_and &= biased(t[u]);
+            TaserRec r;
+            r.ts = t[u];
+            r.nbr = dn[u];
+            r.eid = e[u];
+            rec[i] = r;
+            key[i] = s[u];
+        }
     }
     for (int d = 1; d < kWave; d <<= 1) {
         any_or |= __shfl_xor(any_or, d, kWave);
         all_and &= __shfl_xor(all_and, d, kWave);
     }
-    // one set of atomics per block, not per wave: they all land on the same four words
     __shared__ unsigned long long w_or[kWaves], w_and[kWaves];
     __shared__ int w_bad[kWaves], w_unsorted[kWaves];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
@@ -87,26 +118,36 @@ __global__ __launch_bounds__(kThreads) void inspect_kernel(const int32_t* __rest
             b |= w_bad[w];
             u |= w_unsorted[w];
         }
-        if (b) atomicOr(&info[0], 1ull);
-        if (u) atomicOr(&info[1], 1ull);
-        atomicOr(&info[2], o);
-        atomicAnd(&info[3], a);
+        partial[4 * blockIdx.x + 0] = (unsigned long long)b;
+        partial[4 * blockIdx.x + 1] = (unsigned long long)u;
+        partial[4 * blockIdx.x + 2] = o;
+        partial[4 * blockIdx.x + 3] = a;
     }
 }
 
-__global__ __launch_bounds__(kThreads) void pack_kernel(const int32_t* __restrict__ src,
-                                                        const int32_t* __restrict__ dst,
-                                                        const int64_t* __restrict__ ts,
-                                                        const int32_t* __restrict__ eid, int64_t n,
-                                                        TaserRec* __restrict__ rec, int32_t* __restrict__ key) {
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= n) return;
-    TaserRec r;
-    r.ts = ts[i];
-    r.nbr = dst[i];
-    r.eid = eid ? eid[i] : (int32_t)i;
-    rec[i] = r;
-    key[i] = src[i];
+// info[4 * block + 0..3] = this block's share of the `blocks` per-block word groups of
+// pack_inspect_kernel combined (launched twice: many blocks, then one over their results).
+__global__ __launch_bounds__(kThreads) void fold_info_kernel(const unsigned long long* __restrict__ partial, uint32_t blocks,
+                                                             unsigned long long* __restrict__ info) {
+    __shared__ unsigned long long part[4][kThreads];
+    unsigned long long v[4] = {0, 0, 0, ~0ull};
+    for (uint32_t b = blockIdx.x * kThreads + threadIdx.x; b < blocks; b += gridDim.x * kThreads) {
+        v[0] |= partial[4 * (size_t)b + 0];
+        v[1] |= partial[4 * (size_t)b + 1];
+        v[2] |= partial[4 * (size_t)b + 2];
+        v[3] &= partial[4 * (size_t)b + 3];
+    }
+    for (int j = 0; j < 4; ++j) part[j][threadIdx.x] = v[j];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int t = 1; t < kThreads; ++t) {
+            v[0] |= part[0][t];
+            v[1] |= part[1][t];
+            v[2] |= part[2][t];
+            v[3] &= part[3][t];
+        }
+        for (int j = 0; j < 4; ++j) info[4 * blockIdx.x + j] = v[j];
+    }
 }
 
 // hist[bin * num_blocks + block] = items of this block's tile whose digit is bin.
@@ -129,13 +170,21 @@ __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const TaserRec* __
 }
 
 // Stable scatter of one tile. offs = the scanned histogram: offs[bin*num_blocks
-// + block] is where this block's first item with digit `bin` goes.
+// + block] is where this block's first item with digit `bin` goes. The tile is
+// first put in digit order in LDS (stable: rank among equal digits = ballots
+// inside a row of 64 + running per-wave counters + the waves before), then
+// written out in that order, so that consecutive lanes write consecutive
+// addresses of one digit's run instead of 64 scattered records.
 __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
     const TaserRec* __restrict__ rec_in, const int32_t* __restrict__ key_in, int64_t n, DigitSpec d,
     const uint32_t* __restrict__ offs, uint32_t num_blocks, TaserRec* __restrict__ rec_out,
     int32_t* __restrict__ key_out) {
     __shared__ uint32_t wave_count[kWaves][kBins];   // items of each wave per digit, then exclusive over waves
-    __shared__ uint32_t block_base[kBins];
+    __shared__ uint32_t block_base[kBins];           // global position of the block's first item of a digit
+    __shared__ uint32_t local_base[kBins];           // position of that item inside the ordered tile
+    __shared__ uint32_t scan_tmp[kWaves];
+    __shared__ TaserRec tile_rec[kTile];
+    __shared__ int32_t tile_key[kTile];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const int64_t tile0 = (int64_t)blockIdx.x * kTile;
     for (int w = 0; w < kWaves; ++w) wave_count[w][threadIdx.x] = 0;
@@ -143,12 +192,24 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
     __syncthreads();
 
     uint32_t digit[kItems], rank[kItems];
+    TaserRec item_rec[kItems];
+    int32_t item_key[kItems];
     const uint64_t below = ((uint64_t)1 << lane) - 1;
 #pragma unroll
     for (int r = 0; r < kItems; ++r) {
         const int64_t i = item_index(tile0, wave, r, lane);
         const bool valid = i < n;
-        const uint32_t dg = valid ? digit_at(rec_in, key_in, i, d) : 0u;
+        if (valid) {
+            item_rec[r] = rec_in[i];
+            item_key[r] = key_in[i];
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kItems; ++r) {
+        const int64_t i = item_index(tile0, wave, r, lane);
+        const bool valid = i < n;
+        uint32_t dg = 0;
+        if (valid) dg = d.from_ts ? (uint32_t)(biased(item_rec[r].ts) >> d.shift) & d.mask : ((uint32_t)item_key[r] >> d.shift) & d.mask;
         // lanes of this row that hold the same digit as me
         uint64_t same = __ballot(valid);
 #pragma unroll
@@ -165,22 +226,51 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
         __builtin_amdgcn_wave_barrier();   // keep the LDS counter update of row r ahead of row r+1's read
     }
     __syncthreads();
-    {   // per digit: exclusive prefix of the wave counts over the waves
+    uint32_t mine_total = 0;
+    {   // per digit: exclusive prefix of the wave counts over the waves; thread b owns digit b
         uint32_t run = 0;
         for (int w = 0; w < kWaves; ++w) {
             const uint32_t c = wave_count[w][threadIdx.x];
             wave_count[w][threadIdx.x] = run;
             run += c;
         }
+        mine_total = run;
+    }
+    {   // exclusive prefix of the digit totals over the digits = where a digit's run starts in the tile
+        uint32_t inc = mine_total;
+        for (int dd = 1; dd < kWave; dd <<= 1) {
+            const uint32_t y = __shfl_up(inc, dd, kWave);
+            if (lane >= dd) inc += y;
+        }
+        if (lane == kWave - 1) scan_tmp[wave] = inc;
+        __syncthreads();
+        uint32_t before = 0;
+        for (int w = 0; w < wave; ++w) before += scan_tmp[w];
+        local_base[threadIdx.x] = before + inc - mine_total;
     }
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < kItems; ++r) {
         const int64_t i = item_index(tile0, wave, r, lane);
         if (i < n) {
-            const uint32_t to = block_base[digit[r]] + wave_count[wave][digit[r]] + rank[r];
-            rec_out[to] = rec_in[i];
-            key_out[to] = key_in[i];
+            const uint32_t at = local_base[digit[r]] + wave_count[wave][digit[r]] + rank[r];
+            tile_rec[at] = item_rec[r];
+            tile_key[at] = item_key[r];
+        }
+    }
+    __syncthreads();
+    const int64_t left = n - tile0;
+    const uint32_t count = left < kTile ? (uint32_t)left : (uint32_t)kTile;   // items of this tile
+#pragma unroll 4
+    for (int r = 0; r < kItems; ++r) {
+        const uint32_t j = (uint32_t)r * kThreads + threadIdx.x;
+        if (j < count) {
+            const TaserRec rr = tile_rec[j];
+            const int32_t kk = tile_key[j];
+            const uint32_t dg = d.from_ts ? (uint32_t)(biased(rr.ts) >> d.shift) & d.mask : ((uint32_t)kk >> d.shift) & d.mask;
+            const uint32_t to = block_base[dg] + (j - local_base[dg]);
+            rec_out[to] = rr;
+            key_out[to] = kk;
         }
     }
 }
@@ -269,18 +359,26 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
         }
     }
 
-    // ---- range check and sort plan
+    // ---- pack into records, range check and sort plan in one pass over the input
+    DevBuf rec_a, key_a, rec_b, key_b, hist, partial, indptr;
+    TASER_HIP_TRY(rec_a.alloc(n * sizeof(TaserRec)));
+    TASER_HIP_TRY(key_a.alloc(n * sizeof(int32_t)));
     unsigned long long info[4] = {0, 0, 0, ~0ull};
     if (n > 0) {
-        DevBuf d_info;
+        const unsigned grid = blocks_for(n, kTile);
+        constexpr unsigned kFoldBlocks = 128;
+        DevBuf d_partial, d_folded, d_info;
+        TASER_HIP_TRY(d_partial.alloc((size_t)grid * 4 * sizeof(unsigned long long)));
+        TASER_HIP_TRY(d_folded.alloc((size_t)kFoldBlocks * 4 * sizeof(unsigned long long)));
         TASER_HIP_TRY(d_info.alloc(sizeof(info)));
-        TASER_HIP_TRY(hipMemcpyAsync(d_info.p, info, sizeof(info), hipMemcpyHostToDevice, stream));
-        unsigned grid = blocks_for(n, kThreads);
-        if (grid > 1024) grid = 1024;
         {
-            TaserProfileSpan span(stream, "tcsr_inspect");
-            hipLaunchKernelGGL(inspect_kernel, dim3(grid), dim3(kThreads), 0, stream, src, ts, n, num_nodes,
-                               d_info.as<unsigned long long>());
+            TaserProfileSpan span(stream, "tcsr_pack_inspect");
+            hipLaunchKernelGGL(pack_inspect_kernel, dim3(grid), dim3(kThreads), 0, stream, src, dst, ts, eid, n, num_nodes,
+                               rec_a.as<TaserRec>(), key_a.as<int32_t>(), d_partial.as<unsigned long long>());
+            hipLaunchKernelGGL(fold_info_kernel, dim3(kFoldBlocks), dim3(kThreads), 0, stream,
+                               d_partial.as<unsigned long long>(), grid, d_folded.as<unsigned long long>());
+            hipLaunchKernelGGL(fold_info_kernel, dim3(1), dim3(kThreads), 0, stream, d_folded.as<unsigned long long>(),
+                               kFoldBlocks, d_info.as<unsigned long long>());
         }
         TASER_HIP_TRY(hipGetLastError());
         TASER_HIP_TRY(hipMemcpyAsync(info, d_info.p, sizeof(info), hipMemcpyDeviceToHost, stream));
@@ -300,20 +398,12 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
         passes.push_back(DigitSpec{0, shift, (1u << width) - 1u});
     }
 
-    // ---- pack, then one stable pass per digit, ping-pong between two buffers
-    DevBuf rec_a, key_a, rec_b, key_b, hist, partial, indptr;
-    TASER_HIP_TRY(rec_a.alloc(n * sizeof(TaserRec)));
-    TASER_HIP_TRY(key_a.alloc(n * sizeof(int32_t)));
+    // ---- one stable pass per digit, ping-pong between two buffers
     TASER_HIP_TRY(indptr.alloc(((size_t)num_nodes + 1) * sizeof(int64_t)));
     const uint32_t num_blocks = blocks_for(n, kTile);
     const int64_t hist_len = (int64_t)kBins * num_blocks;
     const unsigned scan_blocks = taser_scan::num_partials(hist_len);
     if (n > 0) {
-        {
-            TaserProfileSpan span(stream, "tcsr_pack");
-            hipLaunchKernelGGL(pack_kernel, dim3(blocks_for(n, kThreads)), dim3(kThreads), 0, stream, src, dst, ts,
-                               eid, n, rec_a.as<TaserRec>(), key_a.as<int32_t>());
-        }
         if (!passes.empty()) {
             TASER_HIP_TRY(rec_b.alloc(n * sizeof(TaserRec)));
             TASER_HIP_TRY(key_b.alloc(n * sizeof(int32_t)));
