@@ -575,6 +575,21 @@ def test_cache_epoch_end_ties_and_extremes():
             oracle.cache_count(probe, rows, Q)
 
 
+def test_cache_policy_replay_tracks_the_all_knowing_cache():
+    """The replay script of the Fig. 3(b) experiment on a small drifting stream: after the first
+    epoch the policy's hit rate stays close to the cache that knows the epoch's frequencies, and
+    both grow with the cache size."""
+    from paper_2402_05396_amd import cache_policy_replay
+    res = cache_policy_replay.main(["--rows", "3000", "--dim", "8", "--epochs", "4", "--batches", "3",
+                                    "--requests", "60000"])
+    later = {k: v[1:] for k, v in res["ratios"].items()}
+    for rows in later.values():
+        for r in rows:
+            assert r["all_knowing"] - 0.05 < r["hit_rate"] <= r["all_knowing"] + 1e-9
+    assert later["10%"][-1]["hit_rate"] < later["20%"][-1]["hit_rate"] < later["30%"][-1]["hit_rate"]
+    assert res["ratios"]["20%"][0]["hit_rate"] < 0.5 < later["20%"][0]["hit_rate"]          # random start, then learned
+
+
 # ----------------------------------------------------------------------------- adaptive mini-batch selection
 @pytest.mark.parametrize("n", [1, 63, 1024, 1025, 70000, (1 << 20) + 5, 3_000_000])
 def test_selector_draws_and_updates_match_the_oracle(n):
