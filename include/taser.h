@@ -120,7 +120,10 @@ void taser_tcsr_free(taser_tcsr* g);
  *                   TASER_RECENT. Otherwise k successive draws without
  *                   replacement as for TASER_WEIGHTED, the running sum taken
  *                   in list order (oldest entry first). Costs time linear in
- *                   cnt per root (the weights depend on the query time).
+ *                   cnt per root (the weights depend on the query time). The
+ *                   first call with this policy on a graph allocates 8 bytes
+ *                   per entry inside the handle (the timestamps alone) and
+ *                   waits for `hip_stream` once.
  * count[i] = number of filled (leading) slots; the rest are padding.
  * Hop h+1 has one root per slot of hop h, root index i*k + j, node = the
  * sampled neighbor and query time = the sampled interaction's timestamp; a

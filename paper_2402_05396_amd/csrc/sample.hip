@@ -19,6 +19,8 @@
 //     pure function of the inputs, independent of scheduling;
 //   * weighted selection keeps the candidate window in registers (one lane per
 //     candidate) and uses integer prefix sums across the group's lanes.
+#include <mutex>
+
 #include "sampling_device.h"
 #include "taser_internal.h"
 
@@ -187,6 +189,15 @@ __device__ __forceinline__ uint64_t inverse_timespan_weight(int64_t t, int64_t t
     const uint64_t delta = (uint64_t)t - (uint64_t)ts;   // exact difference, >= 1
     if (delta >> 32) return 1;                           // the quotient is 1 (delta = 2^32) or 0
     const uint32_t d = (uint32_t)delta;
+    if (d >= 65536u) {
+        // quotient < 2^16: a single-precision reciprocal (relative error < 2^-21) lands within one of
+        // it; the exact remainder 2^32 - q d says which way to step
+        uint32_t q = (uint32_t)(4294967296.0f * __builtin_amdgcn_rcpf((float)d));
+        const int64_t rem = ((int64_t)1 << 32) - (int64_t)((uint64_t)q * d);
+        if (rem < 0) --q;
+        else if (rem >= (int64_t)d) ++q;
+        return q;
+    }
     const uint32_t q = 0xFFFFFFFFu / d, r = 0xFFFFFFFFu - q * d;   // 2^32 = (2^32 - 1) + 1
     return (uint64_t)q + (r == d - 1u ? 1u : 0u);
 }
@@ -213,22 +224,27 @@ __device__ __forceinline__ uint64_t wave_inclusive_scan64(uint64_t v, int lane) 
 
 constexpr int kTileRows = 8;                      // registers of tile sums per lane
 constexpr int kMaxTiles = kTileRows * kWave;      // tile sums per root
+constexpr int kListThreads = 256;                 // block of the finder that reads whole lists
 
-// One wavefront per root: the weights 1/(t - ts) depend on the query, so the whole
-// valid list has to be read once per root. The list is cut into at most 512 tiles
-// of whole 64-entry rows; pass 1 leaves every tile's weight sum in a register
-// (tile i in lane i % 64, register i / 64). Each of the k draws then walks the tile
-// sums, re-reads only the tile it lands in, and takes the picked weight out of the
-// tile's sum, so a draw costs one tile, not the list.
-__global__ __launch_bounds__(kThreads) void sample_hop_inverse_timespan_kernel(
-    const int64_t* __restrict__ indptr, const TaserRec* __restrict__ rec, const TaserTimeIndex index,
-    const int32_t* __restrict__ roots,
+// One block of four wavefronts per root: the weights 1/(t - ts) depend on the query,
+// so the whole valid list has to be read once per root (from a plain array of the
+// timestamps: half the bytes of the 16-byte records), and one wavefront walking a
+// long list alone waits out a memory round trip every few rows. The list is cut
+// into at most 512 tiles of whole 64-entry rows; in pass 1 the waves take the
+// tiles in turn and leave every tile's weight sum in LDS. The first wave then holds
+// the sums in registers (tile i in lane i % 64, register i / 64) and makes the k
+// draws: each walks the tile sums, re-reads only the tile it lands in, and takes the
+// picked weight out of the tile's sum, so a draw costs one tile, not the list.
+__global__ __launch_bounds__(kListThreads) void sample_hop_inverse_timespan_kernel(
+    const int64_t* __restrict__ indptr, const TaserRec* __restrict__ rec, const int64_t* __restrict__ ts_only,
+    const TaserTimeIndex index, const int32_t* __restrict__ roots,
     const int64_t* __restrict__ times, int64_t num_roots, int32_t num_nodes, int k, uint32_t seed_lo, uint32_t seed_hi,
     uint32_t hop, int32_t* __restrict__ o_nbr, int32_t* __restrict__ o_eid, int64_t* __restrict__ o_ts,
     int32_t* __restrict__ o_count) {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int64_t q = (int64_t)blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
-    if (q >= num_roots) return;   // wave-uniform; the kernel has no block-wide barrier
+    __shared__ uint64_t tile_sum_shared[kMaxTiles];
+    __shared__ int64_t cnt_shared;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int64_t q = blockIdx.x;   // the grid has exactly one block per root
 
     int64_t lo = 0, hi = 0, t = 0;
     const int32_t v = roots[q];
@@ -237,26 +253,34 @@ __global__ __launch_bounds__(kThreads) void sample_hop_inverse_timespan_kernel(
         lo = indptr[v];
         hi = indptr[v + 1];
     }
-    const int64_t cnt = group_cutoff<kWave>(rec, index, lo, hi, t, 0, lane);
+    if (wave == 0) {   // wave-uniform: the search's ballots stay inside the first wave
+        const int64_t c = group_cutoff<kWave>(rec, index, lo, hi, t, 0, lane);
+        if (lane == 0) cnt_shared = c;
+    }
+    __syncthreads();
+    const int64_t cnt = cnt_shared;
     const int64_t out0 = q * k;
     const TaserRec pad = {0, -1, -1};
-    if (cnt <= k) {   // everything, most recent first
-        if (lane < k) store_slot(o_nbr, o_eid, o_ts, out0 + lane, lane < cnt ? rec[lo + cnt - 1 - lane] : pad);
-        if (lane == 0) o_count[q] = (int32_t)cnt;
+    if (cnt <= k) {   // everything, most recent first (block-uniform)
+        if (wave == 0) {
+            if (lane < k) store_slot(o_nbr, o_eid, o_ts, out0 + lane, lane < cnt ? rec[lo + cnt - 1 - lane] : pad);
+            if (lane == 0) o_count[q] = (int32_t)cnt;
+        }
         return;
     }
 
     const int64_t rows = (cnt + kWave - 1) / kWave;                 // 64-entry rows of the valid list
-    const int64_t rows_per_tile = (rows + kMaxTiles - 1) / kMaxTiles;
+    // Rows per tile: every tile costs pass 1 a wave-wide reduction, every draw re-reads about half
+    // a tile with a wave-wide scan per row; the sum is smallest near sqrt(1.2 rows / k). The tiling
+    // never changes a result, only the cost. At most kMaxTiles tiles.
+    int64_t rows_per_tile = (int64_t)__builtin_sqrtf(1.2f * (float)rows / (float)k);
+    if (rows_per_tile < 1) rows_per_tile = 1;
+    if (rows_per_tile * kMaxTiles < rows) rows_per_tile = (rows + kMaxTiles - 1) / kMaxTiles;
     const int tiles = (int)((rows + rows_per_tile - 1) / rows_per_tile);
     const int tile_rows = (tiles + kWave - 1) / kWave;              // registers in use
 
-    // Pass 1: tile sums.
-    uint64_t tile_sum[kTileRows];
-#pragma unroll
-    for (int i = 0; i < kTileRows; ++i) tile_sum[i] = 0;
-    uint64_t total = 0;
-    for (int tile = 0; tile < tiles; ++tile) {
+    // Pass 1: tile sums, the waves taking tiles in turn.
+    for (int tile = wave; tile < tiles; tile += kListThreads / kWave) {
         const int64_t r0 = (int64_t)tile * rows_per_tile;
         const int64_t r1 = r0 + rows_per_tile < rows ? r0 + rows_per_tile : rows;
         uint64_t s = 0;
@@ -266,7 +290,7 @@ __global__ __launch_bounds__(kThreads) void sample_hop_inverse_timespan_kernel(
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int64_t p = (r + i) * kWave + lane;
-                ts4[i] = rec[lo + (p < cnt ? p : cnt - 1)].ts;
+                ts4[i] = ts_only[lo + (p < cnt ? p : cnt - 1)];
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -274,14 +298,23 @@ __global__ __launch_bounds__(kThreads) void sample_hop_inverse_timespan_kernel(
         }
         for (; r < r1; ++r) {
             const int64_t p = r * kWave + lane;
-            if (p < cnt) s += inverse_timespan_weight(t, rec[lo + p].ts);
+            if (p < cnt) s += inverse_timespan_weight(t, ts_only[lo + p]);
         }
         s = wave_sum64(s);
-        total += s;
-#pragma unroll
-        for (int i = 0; i < kTileRows; ++i)
-            if (i == (tile >> 6) && lane == (tile & (kWave - 1))) tile_sum[i] = s;
+        if (lane == 0) tile_sum_shared[tile] = s;
     }
+    __syncthreads();
+    if (wave != 0) return;   // the draws are one wavefront's work
+
+    uint64_t tile_sum[kTileRows];
+    uint64_t total = 0;
+#pragma unroll
+    for (int i = 0; i < kTileRows; ++i) {
+        const int tile = i * kWave + lane;
+        tile_sum[i] = tile < tiles ? tile_sum_shared[tile] : 0;
+        total += tile_sum[i];
+    }
+    total = wave_sum64(total);
 
     // k successive draws; lane j keeps the position picked by draw j.
     uint64_t u = 0;
@@ -316,7 +349,7 @@ __global__ __launch_bounds__(kThreads) void sample_hop_inverse_timespan_kernel(
         for (int64_t r = r0; r < r1 && pick < 0; ++r) {
             const int64_t p = r * kWave + lane;
             uint64_t w = 0;
-            if (p < cnt) w = inverse_timespan_weight(t, rec[lo + p].ts);
+            if (p < cnt) w = inverse_timespan_weight(t, ts_only[lo + p]);
             for (int e = 0; e < j; ++e) {
                 const uint64_t taken = group_get64<kWave>((uint64_t)my_pick, e);
                 if ((uint64_t)p == taken) w = 0;
@@ -340,6 +373,33 @@ __global__ __launch_bounds__(kThreads) void sample_hop_inverse_timespan_kernel(
     }
     if (lane < k) store_slot(o_nbr, o_eid, o_ts, out0 + lane, rec[lo + my_pick]);
     if (lane == 0) o_count[q] = k;
+}
+
+__global__ __launch_bounds__(kThreads) void timestamps_only_kernel(const TaserRec* __restrict__ rec, int64_t n,
+                                                                   int64_t* __restrict__ ts_only) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < n) ts_only[i] = rec[i].ts;
+}
+
+// The plain timestamp array of a graph, made on the first call that needs it. The
+// call that makes it waits for the fill, so later calls on any stream find it ready.
+std::mutex g_ts_only_mutex;
+int ensure_ts_only(const taser_tcsr* g_const, hipStream_t stream) {
+    taser_tcsr* g = const_cast<taser_tcsr*>(g_const);   // a cache inside the handle, not a change of the graph
+    std::lock_guard<std::mutex> lock(g_ts_only_mutex);
+    if (g->ts_only || g->num_entries == 0) return TASER_OK;
+    int64_t* p = nullptr;
+    TASER_HIP_TRY(hipMalloc((void**)&p, (size_t)g->num_entries * sizeof(int64_t)));
+    hipLaunchKernelGGL(timestamps_only_kernel, dim3((unsigned)((g->num_entries + kThreads - 1) / kThreads)), dim3(kThreads),
+                       0, stream, g->rec, g->num_entries, p);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) {
+        (void)hipFree(p);
+        return taser_fail_hip(e, "sample_temporal: building the timestamp array");
+    }
+    g->ts_only = p;
+    return TASER_OK;
 }
 
 template <int POLICY, int G>
@@ -391,6 +451,10 @@ extern "C" int taser_sample_temporal(const taser_tcsr* g, const int32_t* roots, 
     }
     taser_clear_stale_hip_error();
     hipStream_t stream = (hipStream_t)hip_stream;
+    if (policy == TASER_INVERSE_TIMESPAN) {
+        const int rc = ensure_ts_only(g, stream);
+        if (rc != TASER_OK) return rc;
+    }
     const int32_t* cur_roots = roots;
     const int64_t* cur_times = times;
     n = num_roots;
@@ -400,9 +464,9 @@ extern "C" int taser_sample_temporal(const taser_tcsr* g, const int32_t* roots, 
             case TASER_UNIFORM: launch_hop<TASER_UNIFORM>(g, cur_roots, cur_times, n, k, seed, (uint32_t)h, m, edge_weight, out[h], stream); break;
             case TASER_INVERSE_TIMESPAN: {
                 TaserProfileSpan span(stream, "sample_hop_inverse_timespan");
-                const unsigned grid = (unsigned)((n + kThreads / kWave - 1) / (kThreads / kWave));
-                hipLaunchKernelGGL(sample_hop_inverse_timespan_kernel, dim3(grid), dim3(kThreads), 0, stream, g->indptr, g->rec,
-                                   g->time_index, cur_roots, cur_times, n, g->num_nodes, k, (uint32_t)seed, (uint32_t)(seed >> 32),
+                const unsigned grid = (unsigned)n;   // one block per root (n < 2^31)
+                hipLaunchKernelGGL(sample_hop_inverse_timespan_kernel, dim3(grid), dim3(kListThreads), 0, stream, g->indptr, g->rec,
+                                   g->ts_only, g->time_index, cur_roots, cur_times, n, g->num_nodes, k, (uint32_t)seed, (uint32_t)(seed >> 32),
                                    (uint32_t)h, out[h].nbr, out[h].eid, out[h].ts, out[h].count);
                 break;
             }

@@ -49,6 +49,8 @@ struct taser_tcsr {
     TaserRec* rec;     // device TaserRec[num_entries], T-CSR order
     int64_t* time_index_storage;   // one device allocation behind time_index.level[*]
     TaserTimeIndex time_index;
+    int64_t* ts_only;              // device int64[num_entries] or null: the timestamps alone, made on first use by
+                                   // the one finder that reads whole lists (inverse timespan)
 };
 
 static constexpr int kWave = 64;

@@ -468,6 +468,7 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
     g->rec = rec_a.release<TaserRec>();
     g->time_index_storage = index_storage.release<int64_t>();
     g->time_index = index;
+    g->ts_only = nullptr;
     *out = g;
     return TASER_OK;
 }
@@ -500,5 +501,6 @@ extern "C" void taser_tcsr_free(taser_tcsr* g) {
     (void)hipFree(g->indptr);
     (void)hipFree(g->rec);
     (void)hipFree(g->time_index_storage);
+    (void)hipFree(g->ts_only);
     delete g;
 }
