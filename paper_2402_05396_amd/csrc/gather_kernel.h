@@ -31,6 +31,7 @@ template <> __device__ __forceinline__ u32x2 zero_of<u32x2>() { return u32x2{0, 
 constexpr int kThreads = 256;
 constexpr int kUnroll = 4;
 constexpr int kTile = kThreads * kUnroll;   // elements (or 16-byte chunks) per block
+constexpr int kMaxTileRows = kTile * 4 + 2; // output rows a block of the chunk kernel can touch (rows of one dword)
 
 // 16 bytes that are only known to be 4-byte aligned.
 struct __attribute__((packed, aligned(4))) Chunk16 {
@@ -59,6 +60,19 @@ __global__ __launch_bounds__(kThreads) void gather_chunks_kernel(Source source, 
     else row0 = tile / (int64_t)row_dwords;
     const uint32_t col0 = (uint32_t)(tile - row0 * row_dwords);
 
+    // Pass 0: the tokens of every output row this tile touches, loaded once by consecutive
+    // lanes into LDS. Without it each chunk's token is a wave-wide broadcast load at the head of
+    // a chain of two dependent loads, and the kernel's speed follows the latency of the token
+    // array (slower by a third when that array has dropped out of the memory-side cache).
+    __shared__ int32_t tile_key[kMaxTileRows];
+    {
+        int64_t tile_last = tile + kTile * 4 - 1;
+        if (tile_last >= total_dwords) tile_last = total_dwords - 1;
+        const uint32_t e_last = col0 + (uint32_t)(tile_last - tile);   // dword offset from the start of row0
+        const int rows_here = (int)(USE_MAGIC ? __umulhi(e_last, magic) : e_last / row_dwords) + 1;   // <= kMaxTileRows
+        for (int r = threadIdx.x; r < rows_here; r += kThreads) tile_key[r] = source.key(row0 + r);
+        __syncthreads();
+    }
     // Pass 1 (ALU only): output row and column of each of this thread's chunks.
     uint32_t col[kUnroll];
     int64_t row[kUnroll];
@@ -73,15 +87,14 @@ __global__ __launch_bounds__(kThreads) void gather_chunks_kernel(Source source, 
         const bool live = tile + local < total_dwords;
         whole[u] = live && col[u] + 4u <= row_dwords;
         cross[u] = live && !whole[u];
-        if (row[u] > last_row) row[u] = last_row;               // keeps the token load below in bounds
+        if (row[u] > last_row) row[u] = last_row;               // keeps the token read below in bounds
     }
-    // Pass 2: straight-line code, no branches, so that the four token loads and
-    // then the four 16-byte row loads are in flight together. A chunk with
-    // nothing to load here (zero row, row-crossing, past the end) reads 16 zero
-    // bytes instead of branching around the load.
+    // Pass 2: straight-line code, no branches, so that the four 16-byte row loads are in
+    // flight together. A chunk with nothing to load here (zero row, row-crossing, past the
+    // end) reads 16 zero bytes instead of branching around the load.
     int32_t key[kUnroll];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) key[u] = source.key(row[u]);
+    for (int u = 0; u < kUnroll; ++u) key[u] = tile_key[row[u] - row0];
     u32x4 vals[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
@@ -101,7 +114,7 @@ __global__ __launch_bounds__(kThreads) void gather_chunks_kernel(Source source, 
         for (int i = 0; i < 4; ++i) {
             if (c >= row_dwords) { c = 0; ++r; }
             if (d + i < total_dwords) {
-                const uint8_t* base = source.address(source.key(r), r);
+                const uint8_t* base = source.address(tile_key[r - row0], r);
                 if (base) w[i] = ((GlobalU32Ptr)base)[c];
             }
             ++c;
