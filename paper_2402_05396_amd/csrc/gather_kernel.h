@@ -50,7 +50,7 @@ typedef const __attribute__((address_space(1))) uint32_t* GlobalU32Ptr;
 // USE_MAGIC: floor(e / d) = umulhi(e, magic) with magic = ceil(2^32 / d), exact
 // for e * d < 2^32 (the launcher checks that); otherwise a plain division.
 template <typename Source, bool USE_MAGIC>
-__global__ __launch_bounds__(kThreads) void gather_chunks_kernel(Source source, uint32_t row_dwords, uint32_t magic,
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void gather_chunks_kernel(Source source, uint32_t row_dwords, uint32_t magic,
                                                                  int64_t total_dwords, int64_t last_row,
                                                                  const uint8_t* __restrict__ zeros,
                                                                  uint32_t* __restrict__ out) {
