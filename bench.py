@@ -25,8 +25,8 @@ EDGE_PITCH_ELEMS = {186: 192}   # rows padded to whole 128-byte lines where the 
 # HBM traffic per launch of the dominant kernel measured offline with
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/c5_gdelt_shaped_hbm_traffic_pmc.txt: (2 x 336 098.6 + 2 148 939.7) KiB per launch
-    ("C5-gdelt-shaped", "cache_gather_rows"): 2888844000,
+    # profiles/c5_gdelt_shaped_hbm_traffic_pmc.txt: (2 x 339 098.5 + 2 149 574.4) KiB per launch
+    ("C5-gdelt-shaped", "cache_gather_rows"): 2895638000,
 }
 
 
