@@ -373,7 +373,14 @@ def main():
                   f"oracle T-CSR build ({t_build:.1f}s) not included")
         if w.edge_feat is None:
             sample += "; edge-feature gather excluded (the table exists only in device memory)"
+        # the same oracle on one thread, on a twentieth of those roots
+        n1 = max(nr // 20, 1)
+        t0 = time.perf_counter()
+        ref1 = oracle.sample_temporal(g_ref, roots[:n1], times[:n1], k, hops, policy, 42, w.m, w.edge_weight, 1)
+        t_one = time.perf_counter() - t0
+        one_thread = round(sum(int(o["count"].sum()) for o in ref1) / t_one, 1)
         cpu = {"value": round(cpu_neighbors / (t_sample + t_gather), 1), "unit": "neighbors/s", "cores": threads,
+               "one_thread_sampler_neighbors_per_s": one_thread,
                "kind": "oracle", "sample": sample}
 
     result = {
