@@ -177,6 +177,20 @@ def test_tcsr_build_node_count_digits(n_nodes):
     assert_tcsr_equal(g, g_ref)
 
 
+@pytest.mark.parametrize("n", [1, 63, 64, 65, 4095, 4096, 4097, 8192, 12288])
+def test_tcsr_build_sizes_around_the_tile(n):
+    """Entry counts at, just below and just above the sort tile (4096) and the row width (64),
+    sorted and unsorted timestamps, followed by a sampling call that walks the time index."""
+    rng = np.random.default_rng(n)
+    for sorted_ts in (True, False):
+        src, dst, ts, eid = _graph(rng, 37, n, 200, sorted_ts)
+        g, g_ref = build_both(src, dst, ts, eid, 37)
+        assert_tcsr_equal(g, g_ref)
+        roots = rng.integers(0, 37, 100).astype(np.int32)
+        times = rng.integers(-1, 205, 100).astype(np.int64)
+        run_both(g, g_ref, roots, times, 5, 2, T.UNIFORM, seed=n)
+
+
 def test_tcsr_build_empty_and_rejects_bad_ids():
     z32, z64 = torch.zeros(0, dtype=torch.int32), torch.zeros(0, dtype=torch.int64)
     g = T.tcsr_build(z32.cuda(), z32.cuda(), z64.cuda(), None, 5)
