@@ -62,7 +62,7 @@ struct taser_cache {
     int32_t* hash_slot;         // device [hash_size]
     uint32_t hash_mask;
     uint8_t* stage_rows;        // device [miss_size][dev_pitch]
-    int32_t* miss_key;          // device [miss_size], cleared per lookup
+    int32_t* miss_key;          // device [miss_size], all kEmpty between lookups
     uint32_t miss_size;         // 0 or a power of two
     int32_t* loc;               // device [loc_capacity], per-request outcome
     int64_t loc_capacity;

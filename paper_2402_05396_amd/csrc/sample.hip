@@ -9,16 +9,18 @@
 //
 // How it is computed differs from Alg. 2's block-per-root / single-thread
 // binary search / shared-memory bitmap with atomic retry:
-//   * the pivot is found by a cooperative (G+1)-ary search: every round the G
-//     lanes of a root probe one timestamp each and a ballot narrows the range
-//     (G+1)-fold, so a 2^25-entry list needs 5-7 dependent memory rounds
-//     instead of 25;
+//   * the pivot is found by a cooperative 16-ary descent through a small index
+//     of the timestamps: every level 16 lanes of a root read 16 neighboring
+//     entries (one 128-byte line) and a ballot gives the child, so a 2^25-entry
+//     list needs 7 dependent reads of one line each instead of 25 scattered ones;
 //   * selection without replacement is a partial Fisher-Yates shuffle whose
 //     random draws come from a counter-based generator keyed by
 //     (seed, hop, root index, slot). No atomics, no retries: the result is a
 //     pure function of the inputs, independent of scheduling;
 //   * weighted selection keeps the candidate window in registers (one lane per
-//     candidate) and uses integer prefix sums across the group's lanes.
+//     candidate) and uses integer prefix sums across the group's lanes;
+//   * the inverse-timespan finder, whose weights depend on the query time, reads
+//     the whole valid list with a block per root (see its kernel).
 #include <mutex>
 
 #include "sampling_device.h"
