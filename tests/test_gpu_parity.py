@@ -242,6 +242,20 @@ def test_sampler_long_lists_and_ties(policy):
     run_both(g, g_ref, roots, times.astype(np.int64), 10, 2, policy, seed=7, m=25, weight=weight)
 
 
+@pytest.mark.parametrize("policy", [T.RECENT, T.UNIFORM])
+def test_sampler_many_roots(policy):
+    """Three million roots in one call (both lane-group widths of the most-recent finder's
+    launch, tens of thousands of blocks), compared element by element."""
+    rng = np.random.default_rng(33)
+    n_nodes, n = 500, 20000
+    src, dst, ts, eid = _graph(rng, n_nodes, n, 100000)
+    g, g_ref = build_both(src, dst, ts, eid, n_nodes)
+    R = 3_000_001
+    roots = rng.integers(-1, n_nodes, R).astype(np.int32)
+    times = rng.integers(0, 100010, R).astype(np.int64)
+    run_both(g, g_ref, roots, times, 10, 1, policy, seed=9)
+
+
 def test_sampler_weight_extremes():
     """uint32 weights up to 2^32 - 1: the running sums need 64 bits."""
     rng = np.random.default_rng(12)
