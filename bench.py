@@ -383,6 +383,13 @@ def main():
                "one_thread_sampler_neighbors_per_s": one_thread,
                "kind": "oracle", "sample": sample}
 
+    # Bytes a step pulls over the bus: every distinct non-resident row of a batch crosses it once
+    # (counted on the host for batch 0 from the ids the device produced).
+    pcie_bytes = None
+    if cache is not None:
+        ids0 = batches[0]["ids"].cpu().numpy()
+        missing = np.setdiff1d(np.unique(ids0[ids0 >= 0]), hot.numpy())
+        pcie_bytes = int(missing.shape[0]) * node_rb
     result = {
         "metric": "sampled temporal neighbors/sec + gather GB/s (% of HBM peak), 2-hop 10x10",
         "value": round(value, 1), "unit": "neighbors/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -399,6 +406,7 @@ def main():
         "gather_GBps": round(gather_gbps, 1), "gather_frac_of_hbm_peak": round(gather_gbps / HBM_PEAK_GBPS, 4),
         "gather_bytes_per_step": gather_bytes_per_step, "neighbors_per_step": neighbors / args.steps,
         "cache_hit_rate": None if cache is None or sum(hm) == 0 else round(hm[0] / sum(hm), 4),
+        "pcie_bytes_per_step": pcie_bytes,
         "tcsr_build": {"entries": int(w.src.shape[0]), "wall_ms": round(build_wall_ms, 2),
                        "kernel_ms": round(build_dev_ms, 3),
                        "kernels": {n: round(ms, 3) for n, (_, ms) in build_kernels.items()}},
