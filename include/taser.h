@@ -17,6 +17,15 @@
  *   - Return value: TASER_OK (0) or a negative taser_status. Arguments are
  *     validated on the host before anything is launched; on error nothing has
  *     been enqueued and taser_last_error() describes the problem.
+ *   - Graph capture: taser_sample_temporal, taser_gather_features,
+ *     taser_candidate_encodings, taser_select_weighted, taser_selector_draw,
+ *     taser_selector_update and taser_cache_lookup / _prefetch / _gather only
+ *     launch kernels (no memset or copy nodes, no synchronization), so a stream
+ *     that is being captured into a HIP graph can be passed to them. Two calls
+ *     allocate the first time and must have run once before a capture: a cache
+ *     lookup with more requests than any before it on that handle, and the
+ *     first TASER_INVERSE_TIMESPAN call on a graph. The per-kernel timing
+ *     session must be off during a capture.
  *   - Padding: an unused output slot holds nbr = -1, eid = -1, ts = 0; a
  *     negative id given to a gather produces a row of zero bytes.
  */

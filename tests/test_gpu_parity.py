@@ -662,3 +662,55 @@ def test_selector_uniform_start_and_all_zero():
     one = torch.tensor([4321], dtype=torch.int32, device="cuda")
     T.selector_update(s, one, torch.tensor([-1], dtype=torch.int32, device="cuda"))     # 2^32 - 1
     assert T.selector_draw(s, 10, 1, 2).tolist() == [4321] * 10
+
+
+# ----------------------------------------------------------------------------- HIP graph capture
+def test_whole_step_replays_from_a_hip_graph():
+    """Sampling, edge gather and cached node lookup of one step captured into a HIP graph and
+    replayed with new roots written into the same input buffers, with eager work and
+    synchronisations between the replays; every replay equals the oracle. (The per-call state of
+    the library is kernels only: no memset nodes, no allocation once the buffers are warm.)"""
+    w = W.make(1)
+    g, g_ref = build_both(w.src, w.dst, w.ts, w.eid, w.num_nodes)
+    rng = np.random.default_rng(3)
+    node_np = rng.standard_normal((w.num_nodes, 12)).astype(np.float32)
+    node_host = torch.from_numpy(node_np).pin_memory()
+    cache = T.cache_init(node_host, 200, None, seed=5, staging_rows=256)
+    table = dev(w.edge_feat)
+    R, k = 600, 10
+    roots_d = torch.empty(R, dtype=torch.int32, device="cuda")
+    times_d = torch.empty(R, dtype=torch.int64, device="cuda")
+    hit_miss = torch.zeros(2, dtype=torch.int64, device="cuda")
+
+    def step(out=None, edge_out=None, node_out=None):
+        out = T.sample_temporal(g, roots_d, times_d, k, 2, T.UNIFORM, 77, out=out)
+        edge_out = T.gather_features(table, out[1]["eid"].reshape(-1), out=edge_out)
+        node_out = T.cache_lookup(cache, out[1]["nbr"].reshape(-1), out=node_out, hit_miss=hit_miss)
+        return out, edge_out, node_out
+
+    roots, times = w.batches[5]
+    roots_d.copy_(torch.from_numpy(roots))
+    times_d.copy_(torch.from_numpy(times))
+    bufs = step()                                                     # warm-up: every buffer exists afterwards
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(*bufs)
+    torch.cuda.current_stream().wait_stream(side)
+    out, edge_out, node_out = bufs
+    for b in (9, 0, 7, 3):
+        roots, times = w.batches[b]
+        roots_d.copy_(torch.from_numpy(roots))                        # eager work between the replays
+        times_d.copy_(torch.from_numpy(times))
+        hit_miss.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = oracle.sample_temporal(g_ref, roots, times, k, 2, W.UNIFORM, 77, threads=THREADS)
+        assert_hops_equal(out, want)
+        assert edge_out.cpu().numpy().tobytes() == oracle.gather(w.edge_feat, want[1]["eid"].ravel()).tobytes()
+        ids = want[1]["nbr"].ravel()
+        assert node_out.cpu().numpy().tobytes() == oracle.gather(node_np, ids).tobytes()
+        assert tuple(hit_miss.tolist()) == oracle.cache_hits(T.cache_residents(cache).numpy(), w.num_nodes, ids)
