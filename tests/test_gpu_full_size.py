@@ -10,7 +10,7 @@ import oracle
 import paper_2402_05396_amd as T
 from paper_2402_05396_amd import workloads as W
 
-pytestmark = [pytest.mark.gpu, pytest.mark.timeout(600)]
+pytestmark = pytest.mark.gpu
 THREADS = min(16, oracle.max_threads())
 
 
