@@ -21,11 +21,15 @@
  *     taser_candidate_encodings, taser_select_weighted, taser_selector_draw,
  *     taser_selector_update and taser_cache_lookup / _prefetch / _gather only
  *     launch kernels (no memset or copy nodes, no synchronization), so a stream
- *     that is being captured into a HIP graph can be passed to them. Two calls
- *     allocate the first time and must have run once before a capture: a cache
- *     lookup with more requests than any before it on that handle, and the
- *     first TASER_INVERSE_TIMESPAN call on a graph. The per-kernel timing
- *     session must be off during a capture.
+ *     that is being captured into a HIP graph can be passed to them. Three
+ *     things happen on first use only and must have happened before a capture:
+ *     a cache lookup or prefetch with more requests than any before it on that
+ *     handle allocates (and waits for the whole device, see
+ *     taser_cache_prefetch); the first TASER_INVERSE_TIMESPAN call on a graph
+ *     allocates; the first gather of a process on a device looks up the address
+ *     of a constant (taser_cache_init and taser_tcsr_build do that too, so any
+ *     handle made on the device is enough). The per-kernel timing session of
+ *     taser_profile.h must be off during a capture.
  *   - Padding: an unused output slot holds nbr = -1, eid = -1, ts = 0; a
  *     negative id given to a gather produces a row of zero bytes.
  */
@@ -264,7 +268,12 @@ int taser_cache_lookup(taser_cache* c, const int32_t* ids, int64_t n, void* out,
  * must be given the same ids pointer and n as the latest prefetch on this
  * handle (TASER_E_ARG otherwise), must be ordered after it (same stream, or an
  * event), and ids must be unchanged in between. A new prefetch must not start
- * before the previous gather has finished: both use the handle's scratch. */
+ * before the previous gather has finished: both use the handle's scratch.
+ * The handle keeps one 32-bit location per request; a call with a larger n than
+ * any before it on this handle first waits for the whole device
+ * (hipDeviceSynchronize: an earlier gather may still read the old array on any
+ * stream), frees that array and allocates a larger one. A caller that must not
+ * block or allocate in its loop makes one call with its largest n beforehand. */
 int taser_cache_prefetch(taser_cache* c, const int32_t* ids, int64_t n, uint64_t* hit_miss,
                          void* hip_stream);
 int taser_cache_gather(taser_cache* c, const int32_t* ids, int64_t n, void* out, void* hip_stream);
@@ -289,8 +298,10 @@ int taser_cache_tune(taser_cache* c, int32_t stage_blocks, int32_t refresh_befor
  *
  * taser_cache_count_accesses(enable != 0): from now on every lookup/prefetch
  * adds 1 to the counter of each requested row with a valid id (hit or miss).
- * The counters (uint32 per row, device memory, zeroed when first enabled) are
- * allocated on first use; enable == 0 pauses counting and keeps them.
+ * The counters (uint32 per row, device memory, zeroed when first enabled) and
+ * the scratch of taser_cache_epoch_end (two more uint32 per row, one int32 per
+ * cache slot) are allocated when counting is first enabled, so an epoch end
+ * allocates nothing; enable == 0 pauses counting and keeps them.
  *
  * taser_cache_access_counts copies the counters into `counts`
  * (device uint32[rows], caller-allocated), ordered on `hip_stream`.
@@ -349,30 +360,6 @@ int taser_selector_update(taser_selector* s, const int32_t* batch, const uint32_
 int taser_selector_scores(const taser_selector* s, uint32_t* scores, uint64_t* total, void* hip_stream);
 int taser_selector_size(const taser_selector* s, int64_t* n);
 void taser_selector_free(taser_selector* s);
-
-/* ---------------------------------------------------------------------------
- * Optional per-kernel timing, for benchmarks. Between taser_profile_begin and
- * taser_profile_end every kernel the library launches (from the thread that
- * began the session; one session at a time) is bracketed by two HIP events on
- * the stream it runs on. taser_profile_end waits for those events and fills
- * `out` (host, caller-allocated, max_entries structs) with one entry per
- * distinct kernel: its name (static storage), number of launches and summed
- * device time in milliseconds; *num_entries receives the number of entries.
- * At most 65536 launches are recorded per session; later ones are not timed.
- * taser_profile_begin_only(kernel_name) starts a session that brackets only the
- * kernel of that name (as reported by an earlier session; NULL or "" = all):
- * every event pair costs a few microseconds of stream time, which matters when
- * the whole pass is being timed as well.
- * ------------------------------------------------------------------------- */
-typedef struct taser_kernel_time {
-    const char* name;
-    int64_t launches;
-    double total_ms;
-} taser_kernel_time;
-
-int taser_profile_begin(void);
-int taser_profile_begin_only(const char* kernel_name);
-int taser_profile_end(taser_kernel_time* out, int32_t max_entries, int32_t* num_entries);
 
 /* Message for the most recent error on the calling thread (static storage). */
 const char* taser_last_error(void);

@@ -75,6 +75,10 @@ struct taser_cache {
     uint32_t* access_count;            // device [rows] or null: requests per row since the last epoch end
     bool counting;
     uint32_t* block_tally;             // device [2 * kClassifyBlocks]: hits, misses of every classify block
+    // scratch of the epoch-end selection, allocated together with access_count
+    uint32_t *epoch_hist, *epoch_rank, *epoch_pos, *epoch_partial;   // [256], [rows], [rows], [num_partials(rows)]
+    int32_t* epoch_selected;                                         // [capacity]
+    unsigned long long* epoch_overlap;                               // [2]
 };
 
 namespace {
@@ -372,7 +376,8 @@ uint32_t pow2_at_least(uint64_t x) {
 void destroy(taser_cache* c) {
     if (!c) return;
     void* const owned[] = {c->cache_rows, c->hash_key, c->hash_slot, c->stage_rows, c->miss_key,
-                           c->loc, c->resident_dev, c->access_count, c->block_tally};
+                           c->loc, c->resident_dev, c->access_count, c->block_tally, c->epoch_hist, c->epoch_rank,
+                           c->epoch_pos, c->epoch_partial, c->epoch_selected, c->epoch_overlap};
     int at = 0;
     for (void* p : owned) {
         const hipError_t e = p ? hipFree(p) : hipSuccess;
@@ -437,6 +442,7 @@ extern "C" int taser_cache_init(const void* host_table, int64_t rows, int32_t ro
         return taser_fail(TASER_E_ARG, "cache_init: host table is not page-locked, device-mapped host memory");
     }
     hipStream_t stream = (hipStream_t)hip_stream;
+    taser_resolve_device_constants();
 
     taser_cache* c = new (std::nothrow) taser_cache();
     if (!c) return taser_fail(TASER_E_OOM, "cache_init: host allocation failed");
@@ -523,8 +529,8 @@ extern "C" int taser_cache_prefetch(taser_cache* c, const int32_t* ids, int64_t 
     taser_clear_stale_hip_error();
     hipStream_t stream = (hipStream_t)hip_stream;
     if (n > c->loc_capacity) {
-        // grows only; the old buffer may still be in use by earlier work on this stream
-        TASER_HIP_TRY(hipStreamSynchronize(stream));
+        // grows only; the old buffer may still be read by a gather on any stream
+        TASER_HIP_TRY(hipDeviceSynchronize());
         (void)hipFree(c->loc);
         c->loc = nullptr;
         c->loc_capacity = 0;
@@ -602,6 +608,17 @@ extern "C" int taser_cache_count_accesses(taser_cache* c, int32_t enable, void* 
     taser_clear_stale_hip_error();
     hipStream_t stream = (hipStream_t)hip_stream;
     if (enable && !c->access_count) {
+        // the counters and everything the epoch-end selection needs, once (access_count last: it
+        // marks the set as complete; a buffer that a failed earlier attempt left behind is kept)
+#define CACHE_NEED(member, bytes) \
+    if (!c->member) TASER_HIP_TRY(hipMalloc((void**)&c->member, (size_t)(bytes)))
+        CACHE_NEED(epoch_hist, 256 * sizeof(uint32_t));
+        CACHE_NEED(epoch_rank, c->rows * sizeof(uint32_t));
+        CACHE_NEED(epoch_pos, c->rows * sizeof(uint32_t));
+        CACHE_NEED(epoch_partial, taser_scan::num_partials(c->rows) * sizeof(uint32_t));
+        CACHE_NEED(epoch_selected, (c->capacity > 0 ? c->capacity : 1) * sizeof(int32_t));
+        CACHE_NEED(epoch_overlap, 2 * sizeof(unsigned long long));
+#undef CACHE_NEED
         TASER_HIP_TRY(hipMalloc((void**)&c->access_count, (size_t)c->rows * sizeof(uint32_t)));
         hipLaunchKernelGGL(fill_kernel, dim3((unsigned)((c->rows + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,
                            reinterpret_cast<int32_t*>(c->access_count), (uint32_t)c->rows, 0);
@@ -630,21 +647,11 @@ extern "C" int taser_cache_epoch_end(taser_cache* c, int64_t min_overlap, int64_
     int64_t both = k;       // with k == 0 or k == rows the top-k is what is resident
     bool replace = false;
     if (k > 0 && k < rows) {
-        struct Scratch {
-            uint32_t *hist = nullptr, *rank = nullptr, *pos = nullptr, *partial = nullptr;
-            int32_t* selected = nullptr;
-            unsigned long long* overlap = nullptr;
-            ~Scratch() {
-                (void)hipFree(hist); (void)hipFree(rank); (void)hipFree(pos); (void)hipFree(partial);
-                (void)hipFree(selected); (void)hipFree(overlap);
-            }
-        } w;
-        TASER_HIP_TRY(hipMalloc((void**)&w.hist, 256 * sizeof(uint32_t)));
-        TASER_HIP_TRY(hipMalloc((void**)&w.rank, (size_t)rows * sizeof(uint32_t)));
-        TASER_HIP_TRY(hipMalloc((void**)&w.pos, (size_t)rows * sizeof(uint32_t)));
-        TASER_HIP_TRY(hipMalloc((void**)&w.partial, (size_t)taser_scan::num_partials(rows) * sizeof(uint32_t)));
-        TASER_HIP_TRY(hipMalloc((void**)&w.selected, (size_t)k * sizeof(int32_t)));
-        TASER_HIP_TRY(hipMalloc((void**)&w.overlap, sizeof(unsigned long long)));
+        struct {
+            uint32_t *hist, *rank, *pos, *partial;
+            int32_t* selected;
+            unsigned long long* overlap;
+        } w = {c->epoch_hist, c->epoch_rank, c->epoch_pos, c->epoch_partial, c->epoch_selected, c->epoch_overlap};
         TaserProfileSpan span(stream, "cache_epoch_end");
         // radix select: the count t of the k-th most requested row, most significant byte first
         uint32_t prefix = 0;

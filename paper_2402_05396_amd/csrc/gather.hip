@@ -39,6 +39,8 @@ const uint8_t* taser_gather::zero_chunk() {
     return cached[dev];
 }
 
+void taser_resolve_device_constants() { (void)taser_gather::zero_chunk(); }
+
 int taser_launch_gather(const void* table, int64_t rows, int32_t row_bytes, int64_t pitch_bytes, const int32_t* ids,
                         int64_t n, void* out, hipStream_t stream) {
     taser_clear_stale_hip_error();

@@ -6,6 +6,7 @@
 #include <vector>
 
 #include "taser_internal.h"
+#include "taser_profile.h"
 
 namespace {
 

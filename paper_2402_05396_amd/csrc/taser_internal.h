@@ -60,6 +60,11 @@ static constexpr int kWave = 64;
 int taser_launch_gather(const void* table, int64_t rows, int32_t row_bytes, int64_t pitch_bytes,
                         const int32_t* ids, int64_t n, void* out, hipStream_t stream);
 
+// Looks up, for the current device, the addresses of the library's device constants
+// (a symbol lookup the first time; nothing afterwards). Handle-making entry points call
+// it so that later gathers on the device only launch kernels.
+void taser_resolve_device_constants();
+
 // Brackets the kernel launches made during its lifetime with a pair of events
 // on `stream` while a taser_profile_begin/_end session is active; otherwise
 // it does nothing. `name` must have static storage.

@@ -337,6 +337,7 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
     if (num_entries > 0 && (!src || !dst || !ts)) return taser_fail(TASER_E_ARG, "tcsr_build: null src/dst/ts");
     if (flags & ~(uint32_t)TASER_INPUT_ON_DEVICE) return taser_fail(TASER_E_ARG, "tcsr_build: unknown flags 0x%x", flags);
     taser_clear_stale_hip_error();
+    taser_resolve_device_constants();
     hipStream_t stream = (hipStream_t)hip_stream;
     const int64_t n = num_entries;
 

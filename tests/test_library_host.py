@@ -12,7 +12,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "taser.h")).read()
+    inc = os.path.join(ROOT, "include")
+    text = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(taser_[a-z_0-9]+)\s*\(", text)))
 
@@ -22,7 +23,7 @@ def test_library_exports_every_declared_symbol():
     assert len(names) >= 10
     lib = T.lib()
     for n in names:
-        assert hasattr(lib, n), f"{n} is declared in taser.h but not exported"
+        assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
     assert set(T.EXPORTS) == set(names)
 
 
