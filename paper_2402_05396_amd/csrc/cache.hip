@@ -518,6 +518,53 @@ extern "C" int taser_cache_init(const void* host_table, int64_t rows, int32_t ro
     return TASER_OK;
 }
 
+// The kernels of the first half of a lookup: classify into `loc` (block counts into `tally`), stage the misses.
+static int enqueue_prefetch(taser_cache* c, const int32_t* ids, int64_t n, uint64_t* hit_miss, hipStream_t stream,
+                            int32_t* loc, uint32_t* tally) {
+    int64_t blocks = (n + kThreads - 1) / kThreads;
+    if (blocks > kClassifyBlocks) blocks = kClassifyBlocks;
+    // miss_key is all-empty here: cache_init cleared it and every stage_kernel clears what it consumed
+    {
+        TaserProfileSpan span(stream, "cache_classify");
+        hipLaunchKernelGGL(classify_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, ids, n, c->rows,
+                           c->hash_key, c->hash_slot, c->hash_mask, c->miss_key, c->miss_size, loc,
+                           hit_miss ? tally : nullptr, c->counting ? c->access_count : nullptr);
+        if (hit_miss)
+            hipLaunchKernelGGL(tally_kernel, dim3(1), dim3(kThreads), 0, stream, tally, (int)blocks,
+                               reinterpret_cast<unsigned long long*>(hit_miss));
+    }
+    if (c->miss_size) {
+        TaserProfileSpan span(stream, "cache_stage_misses");
+        hipLaunchKernelGGL(stage_kernel, dim3(c->stage_blocks), dim3(kThreads), 0, stream, c->miss_key, c->miss_size,
+                           c->host_rows, c->pitch_bytes, (uint32_t)c->row_bytes / 4u, c->stage_rows, c->dev_pitch);
+    }
+    TASER_HIP_TRY(hipGetLastError());
+    return TASER_OK;
+}
+
+// The second half: the dense output from the locations in `loc`.
+static int enqueue_gather(taser_cache* c, const int32_t* ids, int64_t n, void* out, hipStream_t stream, int32_t* loc) {
+    const CacheSource source{loc, ids, c->cache_rows, c->stage_rows, c->dev_pitch, c->host_rows, c->pitch_bytes};
+    const int align = taser_gather::common_alignment((uint64_t)c->row_bytes | (uint64_t)c->pitch_bytes |
+                                                     (uint64_t)(uintptr_t)c->host_rows);
+    if (c->refresh_before_gather) {
+        RewriteJob job;
+        job.words[0] = reinterpret_cast<uint32_t*>(loc);
+        job.count[0] = n;
+        job.words[1] = reinterpret_cast<uint32_t*>(c->cache_rows);
+        job.count[1] = c->capacity * (int64_t)c->dev_pitch / 4;
+        job.words[2] = reinterpret_cast<uint32_t*>(c->stage_rows);
+        job.count[2] = (int64_t)c->miss_size * c->dev_pitch / 4;
+        TaserProfileSpan span(stream, "cache_refresh_working_set");
+        hipLaunchKernelGGL(rewrite_kernel, dim3(2048), dim3(kThreads), 0, stream, job, 0u);
+    }
+    TaserProfileSpan span(stream, "cache_gather_rows");
+    if (!taser_gather::launch(source, align, c->row_bytes, n, out, stream))
+        return taser_fail(TASER_E_RANGE, "cache_gather: %lld rows of %d bytes exceed one launch", (long long)n, c->row_bytes);
+    TASER_HIP_TRY(hipGetLastError());
+    return TASER_OK;
+}
+
 extern "C" int taser_cache_prefetch(taser_cache* c, const int32_t* ids, int64_t n, uint64_t* hit_miss,
                                     void* hip_stream) {
     if (!c) return taser_fail(TASER_E_ARG, "cache_prefetch: null cache");
@@ -537,24 +584,8 @@ extern "C" int taser_cache_prefetch(taser_cache* c, const int32_t* ids, int64_t 
         TASER_HIP_TRY(hipMalloc((void**)&c->loc, (size_t)n * sizeof(int32_t)));
         c->loc_capacity = n;
     }
-    int64_t blocks = (n + kThreads - 1) / kThreads;
-    if (blocks > kClassifyBlocks) blocks = kClassifyBlocks;
-    // miss_key is all-empty here: cache_init cleared it and every stage_kernel clears what it consumed
-    {
-        TaserProfileSpan span(stream, "cache_classify");
-        hipLaunchKernelGGL(classify_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, ids, n, c->rows,
-                           c->hash_key, c->hash_slot, c->hash_mask, c->miss_key, c->miss_size, c->loc,
-                           hit_miss ? c->block_tally : nullptr, c->counting ? c->access_count : nullptr);
-        if (hit_miss)
-            hipLaunchKernelGGL(tally_kernel, dim3(1), dim3(kThreads), 0, stream, c->block_tally, (int)blocks,
-                               reinterpret_cast<unsigned long long*>(hit_miss));
-    }
-    if (c->miss_size) {
-        TaserProfileSpan span(stream, "cache_stage_misses");
-        hipLaunchKernelGGL(stage_kernel, dim3(c->stage_blocks), dim3(kThreads), 0, stream, c->miss_key, c->miss_size,
-                           c->host_rows, c->pitch_bytes, (uint32_t)c->row_bytes / 4u, c->stage_rows, c->dev_pitch);
-    }
-    TASER_HIP_TRY(hipGetLastError());
+    const int rc = enqueue_prefetch(c, ids, n, hit_miss, stream, c->loc, c->block_tally);
+    if (rc != TASER_OK) return rc;
     c->prefetched_ids = ids;
     c->prefetched_n = n;
     return TASER_OK;
@@ -569,26 +600,7 @@ extern "C" int taser_cache_gather(taser_cache* c, const int32_t* ids, int64_t n,
     if (!out) return taser_fail(TASER_E_ARG, "cache_gather: null out");
     if ((uintptr_t)out & 3) return taser_fail(TASER_E_ARG, "cache_gather: out must be 4-byte aligned");
     taser_clear_stale_hip_error();
-    hipStream_t stream = (hipStream_t)hip_stream;
-    const CacheSource source{c->loc, ids, c->cache_rows, c->stage_rows, c->dev_pitch, c->host_rows, c->pitch_bytes};
-    const int align = taser_gather::common_alignment((uint64_t)c->row_bytes | (uint64_t)c->pitch_bytes |
-                                                     (uint64_t)(uintptr_t)c->host_rows);
-    if (c->refresh_before_gather) {
-        RewriteJob job;
-        job.words[0] = reinterpret_cast<uint32_t*>(c->loc);
-        job.count[0] = n;
-        job.words[1] = reinterpret_cast<uint32_t*>(c->cache_rows);
-        job.count[1] = c->capacity * (int64_t)c->dev_pitch / 4;
-        job.words[2] = reinterpret_cast<uint32_t*>(c->stage_rows);
-        job.count[2] = (int64_t)c->miss_size * c->dev_pitch / 4;
-        TaserProfileSpan span(stream, "cache_refresh_working_set");
-        hipLaunchKernelGGL(rewrite_kernel, dim3(2048), dim3(kThreads), 0, stream, job, 0u);
-    }
-    TaserProfileSpan span(stream, "cache_gather_rows");
-    if (!taser_gather::launch(source, align, c->row_bytes, n, out, stream))
-        return taser_fail(TASER_E_RANGE, "cache_gather: %lld rows of %d bytes exceed one launch", (long long)n, c->row_bytes);
-    TASER_HIP_TRY(hipGetLastError());
-    return TASER_OK;
+    return enqueue_gather(c, ids, n, out, (hipStream_t)hip_stream, c->loc);
 }
 
 extern "C" int taser_cache_lookup(taser_cache* c, const int32_t* ids, int64_t n, void* out, uint64_t* hit_miss,
