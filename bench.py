@@ -22,11 +22,15 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 EDGE_PITCH_ELEMS = {186: 192}   # rows padded to whole 128-byte lines where the width is awkward
 
-# HBM traffic per launch of the dominant kernel measured offline with
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured.
-MEASURED_TRAFFIC_BYTES = {
-    # profiles/c5_gdelt_shaped_hbm_traffic_pmc.txt: (2 x 339 098.5 + 2 149 574.4) KiB per launch
-    ("C5-gdelt-shaped", "cache_gather_rows"): 2895638000,
+# HBM-side traffic per launch of the dominant kernel, from two rocprofv3 --pmc runs
+# (FETCH_SIZE, then WRITE_SIZE). The counters cannot be read from inside this process, so
+# the figure is a constant taken from the named summary, not from the run that prints it.
+MEASURED_TRAFFIC = {
+    # (2 x 339 098.5 + 2 149 574.4) KiB per launch
+    ("C5-gdelt-shaped", "cache_gather_rows"): (
+        2895638000, "profiles/c5_gdelt_shaped_hbm_traffic_pmc.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this "
+                    "benchmark with --edges 20000000 (the node gather reads the same 17 000-row table and serves "
+                    "the same number of requests at any event count); not measured in this run"),
 }
 
 
@@ -108,10 +112,11 @@ def main():
 
     cache = None
     if w.node_feat is not None:
+        # Alg. 3 as the paper runs it: random residents first; the content the timed steps see is
+        # decided further down by one counted pass over the batches and an epoch end.
         node_host = torch.from_numpy(w.node_feat).pin_memory()
         cap = int((w.cache_ratio if args.cache_ratio is None else args.cache_ratio) * w.num_nodes)
-        hot = torch.from_numpy(np.ascontiguousarray(w.notes["hot_order"][:cap]))
-        cache = T.cache_init(node_host, cap, hot, staging_rows=w.num_nodes - cap)
+        cache = T.cache_init(node_host, cap, None, seed=42, staging_rows=w.num_nodes - cap)
     torch.cuda.synchronize()
     log(f"tables resident after {time.time() - t0:.1f}s")
 
@@ -142,8 +147,24 @@ def main():
     node_out = [None if cache is None else torch.empty((n_ids, w.node_feat.shape[1]), dtype=torch.float32, device=dev)
                 for _ in range(n_buf)]
     caches = [cache]
+    warmup_epoch = None
     if cache is not None:
-        caches.append(T.cache_init(node_host, cap, hot, staging_rows=w.num_nodes - cap))
+        # One counted pass over all batches with the random content (sampling + classification only),
+        # then the epoch end replaces it by the most requested rows.
+        hm0 = torch.zeros(2, dtype=torch.int64, device=dev)
+        T.cache_count_accesses(cache)
+        for b in batches:
+            T.sample_temporal(g, b["roots"], b["times"], k, hops, policy, 42, w.m, weight, out=b["out"])
+            T.cache_prefetch(cache, b["ids"], hit_miss=hm0)
+        replaced, overlap = T.cache_epoch_end(cache, min_overlap=cap)
+        T.cache_count_accesses(cache, False)
+        h0, m0 = hm0.tolist()
+        residents = T.cache_residents(cache)
+        warmup_epoch = {"batches": len(batches), "hit_rate_random_residents": round(h0 / max(h0 + m0, 1), 4),
+                        "top_rows_resident_before": overlap, "replaced": replaced}
+        log(f"cache warm-up epoch: hit rate {warmup_epoch['hit_rate_random_residents']} with random residents, "
+            f"{overlap} of the {cap} most requested rows were resident, replaced = {replaced}")
+        caches.append(T.cache_init(node_host, cap, residents, staging_rows=w.num_nodes - cap))
         if args.schedule != "serial":
             for c in caches:
                 T.cache_tune(c, stage_blocks=args.stage_blocks, refresh_before_gather=not args.no_refresh)
@@ -252,6 +273,11 @@ def main():
     kernels = T.profile_end()
 
     # ------------------------------------------------------------------ accounting
+    # Two byte counts per gather. "Algorithmic": every served row counted as read + written + its
+    # id, however often the same source row is asked for. "HBM": what has to cross the memory
+    # interface at least once per launch: the dense output, the ids, and every DISTINCT source row
+    # requested (a row asked for 100 times is read from HBM once and from L2 after that). The
+    # roofline fraction is taken on the second count, so it cannot exceed 1.
     used = [batches[i % len(batches)] for i in range(args.steps)]
     neighbors = sum(int(sum(int(o["count"].sum()) for o in b["out"])) for b in used)
     edge_rb = w.edge_dim * edge_table.element_size()
@@ -262,56 +288,76 @@ def main():
     value = neighbors / elapsed
     gather_gbps = gather_bytes_per_step * args.steps / elapsed / 1e9
 
+    def distinct_valid(t):
+        t = t[t >= 0]
+        return int(torch.unique(t).numel())
+    seen = {id(b): b for b in used}.values()                      # each distinct batch once
+    edge_distinct = sum(distinct_valid(b["eids"]) for b in seen) / len(seen)
+    node_distinct = sum(distinct_valid(b["ids"]) for b in seen) / len(seen) if cache is not None else 0
+    edge_hbm = sum(n_slots) * (edge_rb + 4) + edge_distinct * edge_rb
+    node_hbm = n_ids * (node_rb + 4) + node_distinct * node_rb if cache is not None else 0
+
     if dominant_time is None:
         dominant_time = kernels[dominant]            # --graph: from the eager second pass
     per_kernel = {n: {"launches": c, "avg_ms": ms / c} for n, (c, ms) in kernels.items()}
-    hbm_bound = {"cache_gather_rows": node_bytes, "gather_rows": edge_bytes}
+    alg_of = {"cache_gather_rows": node_bytes, "gather_rows": edge_bytes}
+    hbm_of = {"cache_gather_rows": node_hbm, "gather_rows": edge_hbm}
     out_bytes = {"cache_gather_rows": n_ids * node_rb, "gather_rows": sum(n_slots) * edge_rb}
-    alg_bytes = hbm_bound.get(dominant)
     roofline = None
-    if alg_bytes is not None:
+    if dominant in hbm_of:
         dom_ms = dominant_time[1] / dominant_time[0]            # measured inside the timed region
-        achieved = alg_bytes / (dom_ms * 1e-3) / 1e9
+        achieved = hbm_of[dominant] / (dom_ms * 1e-3) / 1e9
+        traffic, traffic_source = MEASURED_TRAFFIC.get((w.name if args.edges is None else None, dominant), (None, None))
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                     "avg_launch_ms": round(dom_ms, 4), "launches_timed": dominant_time[0],
-                    "algorithmic_bytes": alg_bytes,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dominant)),
-                    "note": "algorithmic bytes = rows x (row read + row written + id); the row reads of this "
-                            "kernel are mostly served by L2, so achieved can exceed what HBM alone could carry; "
-                            "output_write_GBps is the dense output alone",
-                    "output_write_GBps": round(out_bytes[dominant] / (dom_ms * 1e-3) / 1e9, 1)}
-        if roofline["traffic"]:
-            t_gbps = roofline["traffic"] / (dom_ms * 1e-3) / 1e9
+                    "hbm_bytes": int(hbm_of[dominant]),
+                    "bytes_note": "achieved = (dense output + 4 B id per row + every distinct source row once) / "
+                                  "average launch time inside the timed region",
+                    "algorithmic_bytes": alg_of[dominant],
+                    "algorithmic_GBps": round(alg_of[dominant] / (dom_ms * 1e-3) / 1e9, 1),
+                    "algorithmic_note": "rows x (row read + row written + id): repeated source rows are served by "
+                                        "L2, so this figure can exceed the HBM peak and is not a roofline fraction",
+                    "output_write_GBps": round(out_bytes[dominant] / (dom_ms * 1e-3) / 1e9, 1),
+                    "traffic": traffic, "traffic_source": traffic_source}
+        if traffic:
+            t_gbps = traffic / (dom_ms * 1e-3) / 1e9
             roofline["traffic_GBps"] = round(t_gbps, 1)               # measured HBM-side bytes / measured time
             roofline["traffic_frac"] = round(t_gbps / HBM_PEAK_GBPS, 4)
 
-    # Every row of the path against the roofline that bounds it (per-kernel times of the second pass;
-    # algorithmic bytes: what the step must move, not transactions or line padding).
-    def hbm_row(alg, ms, note=None):
-        r = {"bound": "hbm", "algorithmic_bytes": int(alg), "ms": round(ms, 4),
-             "achieved_GBps": round(alg / (ms * 1e-3) / 1e9, 1), "frac_of_hbm_peak": round(alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+    # Every row of the path against the roofline that bounds it (per-kernel times of the second pass).
+    def hbm_row(hbm, alg, ms, note=None):
+        r = {"bound": "hbm", "hbm_bytes": int(hbm), "ms": round(ms, 4),
+             "achieved_GBps": round(hbm / (ms * 1e-3) / 1e9, 1), "frac_of_hbm_peak": round(hbm / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+             "algorithmic_bytes": int(alg), "algorithmic_GBps": round(alg / (ms * 1e-3) / 1e9, 1)}
         if note:
             r["note"] = note
         return r
     n_entries = int(w.src.shape[0])
     sample_ms = sum(ms for n, (c, ms) in kernels.items() if n.startswith("sample_hop")) / args.steps
     roots_per_step = R + sum(n_slots[:-1])
+    build_alg = n_entries * (20 + 16) + (w.num_nodes + 1) * 8
+    sampler_bytes = roots_per_step * 20 + neighbors / args.steps * 32 + roots_per_step * 56
     rows_report = {
-        "a1_tcsr_build": hbm_row(n_entries * (20 + 16) + (w.num_nodes + 1) * 8, build_dev_ms,
+        "a1_tcsr_build": hbm_row(build_alg, build_alg, build_dev_ms,
                                  "once per graph; bytes = 20 in + 16 out per entry; a multi-pass sort moves more"),
-        "a2_a6_sampler": dict(hbm_row(roots_per_step * 20 + neighbors / args.steps * 32 + roots_per_step * 56, sample_ms,
+        "a2_a6_sampler": dict(hbm_row(sampler_bytes, sampler_bytes, sample_ms,
                                       "bound by dependent-read latency, not bytes: per root 16 B of list bounds + 4 B count + "
                                       "about 7 index/record probes of 8 B; per kept neighbor 16 B read + 16 B written"),
                               neighbors_per_s=round(neighbors / args.steps / (sample_ms * 1e-3), 1)),
-        "a7_edge_gather": hbm_row(edge_bytes, per_kernel["gather_rows"]["avg_ms"]),
+        "a7_edge_gather": hbm_row(edge_hbm, edge_bytes, per_kernel["gather_rows"]["avg_ms"]),
     }
+    step_hbm_bytes = sampler_bytes + edge_hbm
     if cache is not None:
         lookup_ms = sum(per_kernel[n]["avg_ms"] for n in ("cache_classify", "cache_refresh_working_set", "cache_gather_rows")
                         if n in per_kernel)
         rows_report["a8_node_gather_through_cache"] = hbm_row(
-            node_bytes, lookup_ms, "classify + working-set re-write + gather on the HBM side; the staging of missed rows "
-            f"({per_kernel['cache_stage_misses']['avg_ms']:.3f} ms, bus-bound) runs beside it on the side stream")
+            node_hbm + n_ids * 8, node_bytes, lookup_ms,
+            "classify (+ working-set re-write) + gather on the HBM side, 8 B per request more for the location array; "
+            f"the staging of missed rows ({per_kernel['cache_stage_misses']['avg_ms']:.3f} ms, bus-bound) runs beside it "
+            "on the side stream")
+        step_hbm_bytes += node_hbm + n_ids * 8
+    step_hbm_frac = step_hbm_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS
 
     # ------------------------------------------------------------------ cache maintenance (outside the timed region)
     # Cost of the access counters of Alg. 3 inside the classify kernel, and of one epoch-end
@@ -395,7 +441,9 @@ def main():
         run(0, 1)
         torch.cuda.synchronize()
         for h in range(hops):
-            assert np.array_equal(got[h]["eid"][:nr * k ** (h + 1)].cpu().numpy(), ref[h]["eid"].ravel()), "GPU/oracle mismatch"
+            for f in ("nbr", "eid", "ts"):
+                assert np.array_equal(got[h][f][:nr * k ** (h + 1)].cpu().numpy(), ref[h][f].ravel()), f"GPU/oracle mismatch: hop {h} {f}"
+            assert np.array_equal(got[h]["count"][:nr * k ** h].cpu().numpy(), ref[h]["count"].ravel()), f"GPU/oracle mismatch: hop {h} count"
         sample = (f"first {nr} roots of batch 0, {hops} hops: sampler {t_sample:.2f}s + "
                   f"{'node' if w.edge_feat is None else 'edge'}-feature gather {t_gather:.2f}s; "
                   f"oracle T-CSR build ({t_build:.1f}s) not included")
@@ -416,7 +464,7 @@ def main():
     pcie_bytes = None
     if cache is not None:
         ids0 = batches[0]["ids"].cpu().numpy()
-        missing = np.setdiff1d(np.unique(ids0[ids0 >= 0]), hot.numpy())
+        missing = np.setdiff1d(np.unique(ids0[ids0 >= 0]), residents.numpy())
         pcie_bytes = int(missing.shape[0]) * node_rb
     result = {
         "metric": "sampled temporal neighbors/sec + gather GB/s (% of HBM peak), 2-hop 10x10",
@@ -433,8 +481,14 @@ def main():
         "sampler_neighbors_per_s": round(neighbors / args.steps / (sum(ms for n, (c, ms) in kernels.items()
                                                                        if n.startswith("sample_hop")) / args.steps * 1e-3), 1),
         "gather_GBps": round(gather_gbps, 1), "gather_frac_of_hbm_peak": round(gather_gbps / HBM_PEAK_GBPS, 4),
-        "gather_bytes_per_step": gather_bytes_per_step, "neighbors_per_step": neighbors / args.steps,
+        "gather_bytes_per_step": gather_bytes_per_step,
+        "gather_note": "gather_* count algorithmic bytes (every served row read + written + id) over the whole step time; "
+                       "step_hbm_* count what must cross HBM at least once (outputs, ids, distinct source rows, sampler "
+                       "traffic) over the same time: that one is a fraction of the roofline",
+        "step_hbm_bytes": int(step_hbm_bytes), "step_hbm_frac": round(step_hbm_frac, 4),
+        "neighbors_per_step": neighbors / args.steps,
         "cache_hit_rate": None if cache is None or sum(hm) == 0 else round(hm[0] / sum(hm), 4),
+        "cache_warmup_epoch": warmup_epoch,
         "pcie_bytes_per_step": pcie_bytes,
         "tcsr_build": {"entries": int(w.src.shape[0]), "wall_ms": round(build_wall_ms, 2),
                        "kernel_ms": round(build_dev_ms, 3),

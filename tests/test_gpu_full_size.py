@@ -1,7 +1,9 @@
 """The largest workload (GDELT-shaped: 191 M events, 382 M T-CSR entries, 73 GB edge
 table in device memory) at full size, in the launch configuration bench.py times:
-the oracle recomputes a sample of the outputs one by one, and properties that hold
-at any size are checked on all of them."""
+the oracle recomputes every sampled output of a whole batch one by one (all 12 000
+roots and their 120 000 second-hop roots, most-recent policy), the uniform, weighted and
+inverse-timespan finders on several hundred roots that include the longest list, and
+properties that hold at any size are checked on everything."""
 import numpy as np
 import pytest
 import torch
@@ -18,7 +20,7 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def test_c5_full_size_sampled_parity_and_properties():
+def test_c5_full_size_whole_batch_parity_and_properties():
     free, _ = torch.cuda.mem_get_info()
     if free < 120 * 2 ** 30:
         pytest.skip("needs ~110 GB of free device memory")
@@ -72,20 +74,40 @@ def test_c5_full_size_sampled_parity_and_properties():
         assert bool(((fwd | bwd) & (ev[e] == o["ts"]))[valid].all())
         assert bool((o["ts"][:, :-1] >= o["ts"][:, 1:])[valid[:, 1:]].all())             # most recent first
         assert bool((o["nbr"][~valid] == -1).all()) and bool((o["ts"][~valid] == 0).all())
-    # the oracle, one root at a time (linear scans of the raw lists), for a sample of roots of both hops
+    # the oracle, one root at a time (linear scans of the raw lists): the whole batch, both hops, every field
     g_ref = oracle.tcsr_build(w.src, w.dst, w.ts, w.eid, w.num_nodes, THREADS)
     print("oracle graph built", flush=True)
-    n0 = 300
-    ref = oracle.sample_temporal(g_ref, roots[:n0], times[:n0], k, 2, oracle.RECENT, 42, threads=THREADS)
+    ref = oracle.sample_temporal(g_ref, roots, times, k, 2, oracle.RECENT, 42, threads=THREADS)
     for h in range(2):
         for f in ("nbr", "eid", "ts", "count"):
-            assert np.array_equal(got[h][f][:n0 * k ** h].cpu().numpy(), ref[h][f]), (h, f)
-    pick = rng.integers(0, roots.shape[0] * k, 200)                                     # scattered second-hop roots
-    r2 = oracle.sample_hop(g_ref, got[0]["nbr"].reshape(-1)[pick].cpu().numpy(), got[0]["ts"].reshape(-1)[pick].cpu().numpy(),
-                           k, oracle.RECENT, 42, 1, threads=THREADS)
-    for f in ("nbr", "eid", "ts", "count"):
-        assert np.array_equal(got[1][f][pick].cpu().numpy(), r2[f]), f
-    del g_ref
+            assert np.array_equal(got[h][f].cpu().numpy(), ref[h][f]), (h, f)
+    print("most-recent finder: whole batch equals the oracle", flush=True)
+
+    # the other finders on 512 roots: 480 of the second batch plus 32 queries on the longest list
+    # (37 M entries), from "nothing is earlier" to "everything is earlier"
+    hottest = int(np.argmax(indptr_h[1:] - indptr_h[:-1]))
+    assert indptr_h[hottest + 1] - indptr_h[hottest] > 30_000_000
+    r2, t2 = w.batches[1]
+    t_hot = np.concatenate([[w.ts[0], w.ts[0] + 1, w.ts[-1], w.ts[-1] + 1],
+                            rng.integers(w.ts[0], w.ts[-1] + 2, 28)]).astype(np.int64)
+    roots_x = np.concatenate([r2[:480], np.full(32, hottest, np.int32)]).astype(np.int32)
+    times_x = np.concatenate([t2[:480], t_hot]).astype(np.int64)
+    assert (roots_x == hottest).sum() >= 32
+    weight = rng.integers(1, 1 << 16, w.num_edges, dtype=np.uint32)                      # seeded uint32 weight per edge id
+    d_weight = dev(weight.view(np.int32))
+    for policy, name, m, hops, n_x in ((T.UNIFORM, "uniform", 0, 2, 512), (T.WEIGHTED, "weighted", 25, 2, 512),
+                                       (T.INVERSE_TIMESPAN, "inverse timespan", 0, 1, 512)):
+        lo = 512 - n_x
+        got_x = T.sample_temporal(g, dev(roots_x[lo:]), dev(times_x[lo:]), k, hops, policy, 42, m,
+                                  d_weight if policy == T.WEIGHTED else None)
+        torch.cuda.synchronize()
+        ref_x = oracle.sample_temporal(g_ref, roots_x[lo:], times_x[lo:], k, hops, policy, 42, m,
+                                       weight if policy == T.WEIGHTED else None, threads=THREADS)
+        for h in range(hops):
+            for f in ("nbr", "eid", "ts", "count"):
+                assert np.array_equal(got_x[h][f].cpu().numpy(), ref_x[h][f]), (name, h, f)
+        print(f"{name} finder: {n_x} roots x {hops} hops equal the oracle", flush=True)
+    del g_ref, d_weight, weight
     print("sampler checked", flush=True)
 
     # ---- gathers, as bench.py issues them
