@@ -19,8 +19,9 @@
  *     been enqueued and taser_last_error() describes the problem.
  *   - Graph capture: taser_sample_temporal, taser_gather_features,
  *     taser_candidate_encodings, taser_select_weighted, taser_selector_draw,
- *     taser_selector_update and taser_cache_lookup / _prefetch / _gather only
- *     launch kernels (no memset or copy nodes, no synchronization), so a stream
+ *     taser_selector_update and taser_cache_lookup / _lookup_static /
+ *     _prefetch / _gather only launch kernels (no memset or copy nodes, no
+ *     synchronization), so a stream
  *     that is being captured into a HIP graph can be passed to them. Three
  *     things happen on first use only and must have happened before a capture:
  *     a cache lookup or prefetch with more requests than any before it on that
@@ -70,6 +71,7 @@ enum taser_build_flags {
 #define TASER_MAX_K 64    /* neighbors kept per root and hop              */
 #define TASER_MAX_M 64    /* candidate window of the weighted policy      */
 #define TASER_MAX_HOPS 3
+#define TASER_STATIC_LOOKUP_MAX_REQUESTS (1 << 21) /* requests per taser_cache_lookup_static call */
 
 /* ---------------------------------------------------------------------------
  * T-CSR (Sec. 3.3: the dynamic graph is stored with every node's outgoing
@@ -277,6 +279,25 @@ int taser_cache_lookup(taser_cache* c, const int32_t* ids, int64_t n, void* out,
 int taser_cache_prefetch(taser_cache* c, const int32_t* ids, int64_t n, uint64_t* hit_miss,
                          void* hip_stream);
 int taser_cache_gather(taser_cache* c, const int32_t* ids, int64_t n, void* out, void* hip_stream);
+
+/* taser_cache_lookup for callers that cannot allocate device memory: code whose
+ * stream is being captured into a HIP graph, tight serving loops, harnesses
+ * that forbid hipMalloc. Same arguments, same output and same counters as
+ * taser_cache_lookup, but the per-request scratch (one 32-bit location per
+ * request, per-block hit/miss counts) lives in a fixed array inside the
+ * library's code object (8 MiB + 16 KiB on every GPU the library runs on, held
+ * until the process ends) instead of the handle's growable buffer, so the call
+ * never allocates, frees or synchronizes: it only launches kernels.
+ *   n at most TASER_STATIC_LOOKUP_MAX_REQUESTS, else TASER_E_RANGE (nothing is
+ *   launched).
+ * All handles on one GPU share that array and it keeps the previous call's
+ * contents (every word is written before it is read, nothing has to start at
+ * zero): two such calls that overlap in time on one GPU, on any handles or
+ * streams, race; order them on one stream or by events. The handle's staging
+ * area is used as by taser_cache_lookup, so a taser_cache_prefetch still
+ * waiting for its taser_cache_gather on this handle is cancelled. */
+int taser_cache_lookup_static(taser_cache* c, const int32_t* ids, int64_t n, void* out,
+                              uint64_t* hit_miss, void* hip_stream);
 
 /* Two knobs for callers that run the halves of a lookup beside other kernels.
  *   stage_blocks  number of 256-thread blocks the host -> staging copy runs on

@@ -19,7 +19,7 @@ INPUT_ON_DEVICE = 1
 MAX_K, MAX_M, MAX_HOPS = 64, 64, 3
 
 EXPORTS = ("taser_tcsr_build", "taser_tcsr_size", "taser_tcsr_view", "taser_tcsr_free", "taser_sample_temporal",
-           "taser_candidate_encodings", "taser_select_weighted", "taser_gather_features", "taser_cache_init", "taser_cache_lookup", "taser_cache_prefetch", "taser_cache_gather", "taser_cache_tune", "taser_cache_count_accesses", "taser_cache_access_counts",
+           "taser_candidate_encodings", "taser_select_weighted", "taser_gather_features", "taser_cache_init", "taser_cache_lookup", "taser_cache_lookup_static", "taser_cache_prefetch", "taser_cache_gather", "taser_cache_tune", "taser_cache_count_accesses", "taser_cache_access_counts",
            "taser_cache_epoch_end", "taser_cache_residents",
            "taser_cache_free", "taser_selector_init", "taser_selector_draw", "taser_selector_update",
            "taser_selector_scores", "taser_selector_size", "taser_selector_free", "taser_profile_begin", "taser_profile_begin_only", "taser_profile_end", "taser_last_error")
@@ -65,6 +65,7 @@ def lib():
         L.taser_gather_features.argtypes = [vp, i64, i32, i64, vp, i64, vp, vp]
         L.taser_cache_init.argtypes = [vp, i64, i32, i64, i64, vp, u64, i64, vp, ctypes.POINTER(vp)]
         L.taser_cache_lookup.argtypes = [vp, vp, i64, vp, vp, vp]
+        L.taser_cache_lookup_static.argtypes = [vp, vp, i64, vp, vp, vp]
         L.taser_cache_prefetch.argtypes = [vp, vp, i64, vp, vp]
         L.taser_cache_gather.argtypes = [vp, vp, i64, vp, vp]
         L.taser_cache_tune.argtypes = [vp, i32, i32]
@@ -313,6 +314,18 @@ def cache_lookup(c, ids, out=None, hit_miss=None, stream=None):
     if hit_miss is not None:
         _want(hit_miss, torch.int64, "hit_miss")
     _check(lib().taser_cache_lookup(c.handle, _ptr(ids), n, _ptr(out), _ptr(hit_miss), _stream(stream)))
+    return out
+
+
+def cache_lookup_static(c, ids, out, hit_miss=None, stream=None):
+    """taser_cache_lookup_static: the lookup that allocates nothing (`out` must be given)."""
+    _want(ids, torch.int32, "ids")
+    n = ids.numel()
+    if out.dtype != c.host_table.dtype or not out.is_contiguous() or out.numel() < n * c.row_elems:
+        raise TypeError("out: expected a contiguous device tensor of the table's dtype with n*d elements")
+    if hit_miss is not None:
+        _want(hit_miss, torch.int64, "hit_miss")
+    _check(lib().taser_cache_lookup_static(c.handle, _ptr(ids), n, _ptr(out), _ptr(hit_miss), _stream(stream)))
     return out
 
 

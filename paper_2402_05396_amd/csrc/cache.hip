@@ -22,6 +22,7 @@
 //      miss table full.
 // Which rows are resident only changes where bytes come from, never the bytes.
 #include <cstdio>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -422,6 +423,37 @@ int install_residents(taser_cache* c, hipStream_t stream) {
 
 }  // namespace
 
+// ---- lookup that allocates nothing ---------------------------------------------
+// Per-request locations and per-block hit/miss counts of taser_cache_lookup_static live
+// in this array instead of the handle's growable buffers. Every GPU holds its own copy;
+// host code reaches it only through the address looked up once per device below.
+constexpr int64_t kStaticRequests = TASER_STATIC_LOOKUP_MAX_REQUESTS;
+static __device__ __align__(256) int32_t scratch[kStaticRequests + 2 * kClassifyBlocks];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+int32_t* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each GPU, null until looked up
+
+// Address of `scratch` on the current device (looked up the first time, with that device current).
+int scratch_on_current_device(int32_t** out) {
+    int dev = -1;
+    TASER_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return taser_fail(TASER_E_RANGE, "cache: device ordinal %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        TASER_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return taser_fail(TASER_E_HIP, "cache: the lookup scratch has no address on device %d", dev);
+        g_scratch_ptr[dev] = static_cast<int32_t*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return TASER_OK;
+}
+
+}  // namespace
+
 extern "C" int taser_cache_init(const void* host_table, int64_t rows, int32_t row_bytes, int64_t pitch_bytes,
                                 int64_t capacity_rows, const int32_t* resident_ids, uint64_t seed,
                                 int64_t staging_rows, void* hip_stream, taser_cache** out) {
@@ -443,6 +475,11 @@ extern "C" int taser_cache_init(const void* host_table, int64_t rows, int32_t ro
     }
     hipStream_t stream = (hipStream_t)hip_stream;
     taser_resolve_device_constants();
+    {
+        int32_t* unused = nullptr;   // the allocation-free lookup's scratch gets its address on this device now
+        const int rc = scratch_on_current_device(&unused);
+        if (rc != TASER_OK) return rc;
+    }
 
     taser_cache* c = new (std::nothrow) taser_cache();
     if (!c) return taser_fail(TASER_E_OOM, "cache_init: host allocation failed");
@@ -613,6 +650,30 @@ extern "C" int taser_cache_lookup(taser_cache* c, const int32_t* ids, int64_t n,
     const int rc = taser_cache_prefetch(c, ids, n, hit_miss, hip_stream);
     if (rc != TASER_OK) return rc;
     return taser_cache_gather(c, ids, n, out, hip_stream);
+}
+
+extern "C" int taser_cache_lookup_static(taser_cache* c, const int32_t* ids, int64_t n, void* out, uint64_t* hit_miss,
+                                         void* hip_stream) {
+    if (!c) return taser_fail(TASER_E_ARG, "cache_lookup_static: null cache");
+    if (n < 0) return taser_fail(TASER_E_ARG, "cache_lookup_static: n = %lld", (long long)n);
+    if (n > kStaticRequests)
+        return taser_fail(TASER_E_RANGE, "cache_lookup_static: n = %lld exceeds the %lld requests its fixed scratch holds",
+                          (long long)n, (long long)kStaticRequests);
+    if (n == 0) return TASER_OK;
+    if (!ids || !out) return taser_fail(TASER_E_ARG, "cache_lookup_static: null ids or out");
+    if ((uintptr_t)out & 3) return taser_fail(TASER_E_ARG, "cache_lookup_static: out must be 4-byte aligned");
+    taser_clear_stale_hip_error();
+    int32_t* base = nullptr;
+    int rc = scratch_on_current_device(&base);
+    if (rc != TASER_OK) return rc;
+    int32_t* loc = base;                                                     // [n]: written before it is read
+    uint32_t* tally = reinterpret_cast<uint32_t*>(base + kStaticRequests);   // [2 * blocks]: likewise
+    c->prefetched_ids = nullptr;   // the handle's miss table and staging rows are reused: a pending prefetch is void
+    c->prefetched_n = 0;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    rc = enqueue_prefetch(c, ids, n, hit_miss, stream, loc, tally);
+    if (rc != TASER_OK) return rc;
+    return enqueue_gather(c, ids, n, out, stream, loc);
 }
 
 extern "C" int taser_cache_count_accesses(taser_cache* c, int32_t enable, void* hip_stream) {

@@ -97,6 +97,10 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert lib.taser_cache_init(one, 4, 16, 16, 5, None, 0, 0, None, ctypes.byref(c)) == E_RANGE
     assert lib.taser_cache_init(one, 4, 16, 16, 1, None, 0, -1, None, ctypes.byref(c)) == E_RANGE
     assert lib.taser_cache_lookup(None, one, 1, one, None, None) == E_ARG
+    assert lib.taser_cache_lookup_static(None, one, 1, one, None, None) == E_ARG
+    assert lib.taser_cache_lookup_static(one, one, -1, one, None, None) == E_ARG
+    assert lib.taser_cache_lookup_static(one, one, (1 << 21) + 1, one, None, None) == E_RANGE   # beyond its fixed scratch
+    assert "exceeds" in T.last_error()
     assert lib.taser_cache_prefetch(None, one, 1, None, None) == E_ARG
     assert lib.taser_cache_gather(None, one, 1, one, None) == E_ARG
     assert lib.taser_cache_tune(None, 1, 0) == E_ARG
