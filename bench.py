@@ -51,8 +51,9 @@ def main():
     ap.add_argument("--policy", default=None, choices=["recent", "uniform", "weighted", "inverse_timespan"],
                     help="override the workload's selection policy (then it is not the named workload)")
     ap.add_argument("--graph", action="store_true",
-                    help="workloads without a node cache only: capture the timed steps into one HIP graph and time its "
-                         "replay (the roofline kernel's time then comes from the second, eager pass)")
+                    help="capture the timed steps (both streams, forked and joined by events inside the capture) into "
+                         "one HIP graph and time its replay (the roofline kernel's time then comes from the second, "
+                         "eager pass)")
     ap.add_argument("--no-refresh", action="store_true", help="do not re-write the gather's working set before the node gather")
     ap.add_argument("--cache-ratio", type=float, default=None,
                     help="override the share of node rows resident in the device cache (then it is not the named workload)")
@@ -237,8 +238,6 @@ def main():
     # Only the dominant kernel is bracketed by events here: 16 event records per step on
     # two streams cost about 5 % of the step, two cost next to nothing.
     if args.graph:
-        if cache is not None:
-            ap.error("--graph is for the workloads without a node cache")
         capture = torch.cuda.Stream()
         capture.wait_stream(main)
         graph = torch.cuda.CUDAGraph()
@@ -334,7 +333,7 @@ def main():
             r["note"] = note
         return r
     n_entries = int(w.src.shape[0])
-    sample_ms = sum(ms for n, (c, ms) in kernels.items() if n.startswith("sample_hop")) / args.steps
+    sample_ms = sum(ms for n, (c, ms) in kernels.items() if n.startswith("sample_")) / args.steps
     roots_per_step = R + sum(n_slots[:-1])
     build_alg = n_entries * (20 + 16) + (w.num_nodes + 1) * 8
     sampler_bytes = roots_per_step * 20 + neighbors / args.steps * 32 + roots_per_step * 56
@@ -479,7 +478,7 @@ def main():
                    else f"{cache.capacity} (override)", "schedule": args.schedule,
                    "launch": "one HIP graph of all timed steps" if args.graph else "eager"},
         "sampler_neighbors_per_s": round(neighbors / args.steps / (sum(ms for n, (c, ms) in kernels.items()
-                                                                       if n.startswith("sample_hop")) / args.steps * 1e-3), 1),
+                                                                       if n.startswith("sample_")) / args.steps * 1e-3), 1),
         "gather_GBps": round(gather_gbps, 1), "gather_frac_of_hbm_peak": round(gather_gbps / HBM_PEAK_GBPS, 4),
         "gather_bytes_per_step": gather_bytes_per_step,
         "gather_note": "gather_* count algorithmic bytes (every served row read + written + id) over the whole step time; "

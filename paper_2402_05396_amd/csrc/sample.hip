@@ -118,21 +118,19 @@ __device__ __forceinline__ void store_slot(int32_t* o_nbr, int32_t* o_eid, int64
 
 constexpr int kThreads = 256;
 
-// Selection for one root whose cutoff is known; every lane of the wave must call it.
+// Selection for one root whose cutoff is known. Returns, in lane `sub` of the root's group, the
+// record of output slot `sub` (padding from slot `filled` on); every lane of the wave must call it.
 template <int POLICY, int G>
-__device__ __forceinline__ void select_and_store(
-    const TaserRec* __restrict__ rec, int64_t q, bool live, int64_t lo, int64_t cnt, int group, int sub, int k,
-    uint32_t seed_lo, uint32_t seed_hi, uint32_t hop, int m, const uint32_t* __restrict__ edge_weight,
-    int32_t* __restrict__ o_nbr, int32_t* __restrict__ o_eid, int64_t* __restrict__ o_ts,
-    int32_t* __restrict__ o_count) {
-    const int64_t out0 = q * k;
+__device__ __forceinline__ TaserRec select_slot(
+    const TaserRec* __restrict__ rec, int64_t q, int64_t lo, int64_t cnt, int group, int sub, int k,
+    uint32_t seed_lo, uint32_t seed_hi, uint32_t hop, int m, const uint32_t* __restrict__ edge_weight, int& filled) {
     const TaserRec pad = {0, -1, -1};
-    int filled = 0;
+    TaserRec out = pad;
 
     // All lanes of the wave walk through the same code; what a group does not need is masked.
     if (POLICY == TASER_RECENT) {
         filled = (int)(cnt < k ? cnt : k);
-        if (live && sub < k) store_slot(o_nbr, o_eid, o_ts, out0 + sub, sub < filled ? rec[lo + cnt - 1 - sub] : pad);
+        if (sub < filled) out = rec[lo + cnt - 1 - sub];
     } else if (POLICY == TASER_UNIFORM) {
         // cnt <= k: everything, most recent first. Otherwise a partial Fisher-Yates
         // over the virtual array a[x] = x, x in [0, cnt): lane j of the group owns
@@ -161,14 +159,13 @@ __device__ __forceinline__ void select_and_store(
                 }
             }
         }
-        if (live && sub < k) {
-            TaserRec r = pad;
-            if (shuffle) r = rec[lo + idx];
-            else if (sub < filled) r = rec[lo + cnt - 1 - sub];
-            store_slot(o_nbr, o_eid, o_ts, out0 + sub, r);
+        if (sub < k) {
+            if (shuffle) out = rec[lo + idx];
+            else if (sub < filled) out = rec[lo + cnt - 1 - sub];
         }
     } else {
-        // Candidate window: lane i of the group holds candidate i (the i-th most recent).
+        // Candidate window: lane i of the group holds candidate i (the i-th most recent);
+        // lane j notes which candidate draw j picked and fetches it from that lane at the end.
         const int c = (int)(cnt < m ? cnt : m);
         TaserRec mine = pad;
         uint64_t w = 0;
@@ -178,30 +175,25 @@ __device__ __forceinline__ void select_and_store(
         }
         const bool draw = c > k;
         filled = draw ? k : c;
-        if (!draw && live && sub < k) store_slot(o_nbr, o_eid, o_ts, out0 + sub, mine);
+        int my_pick = (!draw && sub < c) ? sub : -1;
         if (__ballot(draw)) {
             uint64_t u = 0;
             if (draw && sub < k) u = draw64(seed_lo, seed_hi, hop, (uint64_t)q, (uint32_t)sub);
+            // running sums of the weights once; every draw then only takes its pick out of them
+            uint64_t run = group_inclusive_scan64<G>(w, sub);
+            uint64_t total = group_get64<G>(run, G - 1);
             for (int j = 0; j < k; ++j) {
-                uint64_t run = w;   // inclusive prefix sum of the remaining weights inside the group
-#pragma unroll
-                for (int d = 1; d < G; d <<= 1) {
-                    const uint32_t lo32 = __shfl_up((uint32_t)run, d, G);
-                    const uint32_t hi32 = __shfl_up((uint32_t)(run >> 32), d, G);
-                    if (sub >= d) run += ((uint64_t)hi32 << 32) | lo32;
-                }
-                const uint64_t total = group_get64<G>(run, G - 1);
-                const uint64_t x = __umul64hi(group_get64<G>(u, j), total);
-                const uint64_t above = group_bits<G>(__ballot(draw && run > x), group);
-                const int pick = __ffsll((long long)above) - 1;
-                if (draw && sub == pick) {
-                    store_slot(o_nbr, o_eid, o_ts, out0 + j, mine);
-                    w = 0;
-                }
+                const int pick = group_weighted_pick<G>(run, total, w, group_get64<G>(u, j), draw, group, sub);
+                if (draw && sub == j) my_pick = pick;
             }
         }
+        const int from = my_pick < 0 ? 0 : my_pick;   // the shuffles are executed by every lane
+        const int32_t p_nbr = (int32_t)group_get<G>((uint32_t)mine.nbr, from);
+        const int32_t p_eid = (int32_t)group_get<G>((uint32_t)mine.eid, from);
+        const int64_t p_ts = (int64_t)group_get64<G>((uint64_t)mine.ts, from);
+        if (my_pick >= 0 && sub < k) out = TaserRec{p_ts, p_nbr, p_eid};
     }
-    if (live && sub == 0) o_count[q] = filled;
+    return out;
 }
 
 // G lanes per root: G >= k, and G >= m for the weighted policy. A group serves
@@ -236,11 +228,16 @@ __global__ __launch_bounds__(kThreads) void sample_hop_kernel(
         }
     }
     group_cutoff<G, kRootsPerGroup>(rec, index, lo, hi, t, group, sub, cnt);   // 0 for dead roots (lo == hi)
-    // All lanes of the wave walk through the same code; what a group does not need is masked.
 #pragma unroll
-    for (int r = 0; r < kRootsPerGroup; ++r)
-        select_and_store<POLICY, G>(rec, q0 + r, q0 + r < num_roots, lo[r], cnt[r], group, sub, k, seed_lo, seed_hi, hop, m,
-                                    edge_weight, o_nbr, o_eid, o_ts, o_count);
+    for (int r = 0; r < kRootsPerGroup; ++r) {
+        int filled;
+        const TaserRec slot = select_slot<POLICY, G>(rec, q0 + r, lo[r], cnt[r], group, sub, k, seed_lo, seed_hi, hop, m,
+                                                     edge_weight, filled);
+        if (q0 + r < num_roots) {
+            if (sub < k) store_slot(o_nbr, o_eid, o_ts, (q0 + r) * k + sub, slot);
+            if (sub == 0) o_count[q0 + r] = filled;
+        }
+    }
 }
 
 // ---- inverse-timespan finder -------------------------------------------------

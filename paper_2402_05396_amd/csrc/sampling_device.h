@@ -45,4 +45,38 @@ template <int G> __device__ __forceinline__ uint64_t group_get64(uint64_t v, int
     return ((uint64_t)group_get<G>((uint32_t)(v >> 32), sub_lane) << 32) | group_get<G>((uint32_t)v, sub_lane);
 }
 
+// Inclusive prefix sum of one 64-bit value per lane inside a group.
+template <int G> __device__ __forceinline__ uint64_t group_inclusive_scan64(uint64_t v, int sub) {
+#pragma unroll
+    for (int d = 1; d < G; d <<= 1) {
+        const uint32_t lo32 = __shfl_up((uint32_t)v, d, G);
+        const uint32_t hi32 = __shfl_up((uint32_t)(v >> 32), d, G);
+        if (sub >= d) v += ((uint64_t)hi32 << 32) | lo32;
+    }
+    return v;
+}
+
+// One of k successive weighted draws without replacement inside a group whose lane i
+// holds candidate i: `run` is the inclusive prefix sum of the weights still in play,
+// `total` their sum, `w` this lane's weight (below 2^32; 0 once taken), u the 64 random
+// bits of this draw. Returns the lane of the first candidate whose running sum exceeds
+// floor(u * total / 2^64), or -1 when nothing is left, and takes that candidate out:
+// every running sum from its lane on drops by its weight, which is what summing the
+// remaining weights again would give. All lanes of the wave must call this; groups
+// with `active` false are left untouched.
+template <int G>
+__device__ __forceinline__ int group_weighted_pick(uint64_t& run, uint64_t& total, uint64_t& w, uint64_t u, bool active,
+                                                   int group, int sub) {
+    const uint64_t x = __umul64hi(u, total);
+    const uint64_t above = group_bits<G>(__ballot(active && run > x), group);
+    const int pick = __ffsll((long long)above) - 1;
+    const uint64_t taken = group_get<G>((uint32_t)w, pick < 0 ? 0 : pick);   // executed by every lane
+    if (active && pick >= 0) {
+        if (sub >= pick) run -= taken;
+        total -= taken;
+        if (sub == pick) w = 0;
+    }
+    return pick;
+}
+
 }  // namespace

@@ -174,7 +174,13 @@ __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const TaserRec* __
 // first put in digit order in LDS (stable: rank among equal digits = ballots
 // inside a row of 64 + running per-wave counters + the waves before), then
 // written out in that order, so that consecutive lanes write consecutive
-// addresses of one digit's run instead of 64 scattered records.
+// addresses of one digit's run instead of 64 scattered records. The ordered tile
+// passes through LDS in kParts slices (every item knows its place in the order;
+// a slice takes the items whose place falls into it): a whole tile of records
+// and keys, 80 KB, would leave room for one block per compute unit, a slice of
+// half a tile for three, which is what the registers allow.
+constexpr int kParts = 2;
+constexpr int kPart = kTile / kParts;
 __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
     const TaserRec* __restrict__ rec_in, const int32_t* __restrict__ key_in, int64_t n, DigitSpec d,
     const uint32_t* __restrict__ offs, uint32_t num_blocks, TaserRec* __restrict__ rec_out,
@@ -183,8 +189,8 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
     __shared__ uint32_t block_base[kBins];           // global position of the block's first item of a digit
     __shared__ uint32_t local_base[kBins];           // position of that item inside the ordered tile
     __shared__ uint32_t scan_tmp[kWaves];
-    __shared__ TaserRec tile_rec[kTile];
-    __shared__ int32_t tile_key[kTile];
+    __shared__ TaserRec tile_rec[kPart];
+    __shared__ int32_t tile_key[kPart];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const int64_t tile0 = (int64_t)blockIdx.x * kTile;
     for (int w = 0; w < kWaves; ++w) wave_count[w][threadIdx.x] = 0;
@@ -250,28 +256,33 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
     }
     __syncthreads();
 #pragma unroll
-    for (int r = 0; r < kItems; ++r) {
-        const int64_t i = item_index(tile0, wave, r, lane);
-        if (i < n) {
-            const uint32_t at = local_base[digit[r]] + wave_count[wave][digit[r]] + rank[r];
-            tile_rec[at] = item_rec[r];
-            tile_key[at] = item_key[r];
-        }
-    }
-    __syncthreads();
+    for (int r = 0; r < kItems; ++r)   // rank becomes the item's place in the ordered tile
+        if (item_index(tile0, wave, r, lane) < n) rank[r] += local_base[digit[r]] + wave_count[wave][digit[r]];
     const int64_t left = n - tile0;
     const uint32_t count = left < kTile ? (uint32_t)left : (uint32_t)kTile;   // items of this tile
-#pragma unroll 4
-    for (int r = 0; r < kItems; ++r) {
-        const uint32_t j = (uint32_t)r * kThreads + threadIdx.x;
-        if (j < count) {
-            const TaserRec rr = tile_rec[j];
-            const int32_t kk = tile_key[j];
-            const uint32_t dg = d.from_ts ? (uint32_t)(biased(rr.ts) >> d.shift) & d.mask : ((uint32_t)kk >> d.shift) & d.mask;
-            const uint32_t to = block_base[dg] + (j - local_base[dg]);
-            rec_out[to] = rr;
-            key_out[to] = kk;
+    for (uint32_t part0 = 0; part0 < count; part0 += kPart) {
+#pragma unroll
+        for (int r = 0; r < kItems; ++r) {
+            const uint32_t at = rank[r] - part0;   // wraps far beyond kPart for places before this slice
+            if (item_index(tile0, wave, r, lane) < n && at < (uint32_t)kPart) {
+                tile_rec[at] = item_rec[r];
+                tile_key[at] = item_key[r];
+            }
         }
+        __syncthreads();
+#pragma unroll 4
+        for (int r = 0; r < kItems / kParts; ++r) {
+            const uint32_t j = (uint32_t)r * kThreads + threadIdx.x;   // place inside the slice
+            if (part0 + j < count) {
+                const TaserRec rr = tile_rec[j];
+                const int32_t kk = tile_key[j];
+                const uint32_t dg = d.from_ts ? (uint32_t)(biased(rr.ts) >> d.shift) & d.mask : ((uint32_t)kk >> d.shift) & d.mask;
+                const uint32_t to = block_base[dg] + (part0 + j - local_base[dg]);
+                rec_out[to] = rr;
+                key_out[to] = kk;
+            }
+        }
+        __syncthreads();   // the slice is free again
     }
 }
 

@@ -106,9 +106,9 @@ __global__ __launch_bounds__(kThreads) void candidate_encodings_kernel(
 }
 
 // n of m by per-slot weights: lane i of a group holds the weight of candidate i.
-// Each of the k rounds takes a prefix sum of the remaining weights, scales one
-// 64-bit draw to the total and picks the first lane whose running sum exceeds
-// it. Lane j keeps round j's pick, so the outputs are written coalesced at the end.
+// The running sums of the weights are taken once; each of the k rounds scales one
+// 64-bit draw to the remaining total, picks the first lane whose running sum exceeds
+// it and takes that lane's weight out of the sums after it. Lane j keeps round j's pick, so the outputs are written coalesced at the end.
 template <int G>
 __global__ __launch_bounds__(kThreads) void select_weighted_kernel(
     const uint32_t* __restrict__ weight, const int32_t* __restrict__ count, int64_t num_roots, int m, int k,
@@ -134,19 +134,10 @@ __global__ __launch_bounds__(kThreads) void select_weighted_kernel(
     if (__ballot(draw)) {
         uint64_t u = 0;
         if (draw && sub < k) u = draw64(seed_lo, seed_hi, hop, (uint64_t)q, (uint32_t)sub);
+        uint64_t run = group_inclusive_scan64<G>(w, sub);
+        uint64_t total = group_get64<G>(run, G - 1);
         for (int j = 0; j < k; ++j) {
-            uint64_t run = w;
-#pragma unroll
-            for (int d = 1; d < G; d <<= 1) {
-                const uint32_t lo32 = __shfl_up((uint32_t)run, d, G);
-                const uint32_t hi32 = __shfl_up((uint32_t)(run >> 32), d, G);
-                if (sub >= d) run += ((uint64_t)hi32 << 32) | lo32;
-            }
-            const uint64_t total = group_get64<G>(run, G - 1);
-            const uint64_t x = __umul64hi(group_get64<G>(u, j), total);
-            const uint64_t above = group_bits<G>(__ballot(draw && run > x), group);
-            const int pick = __ffsll((long long)above) - 1;   // -1 only if every remaining weight is 0
-            if (draw && sub == pick) w = 0;
+            const int pick = group_weighted_pick<G>(run, total, w, group_get64<G>(u, j), draw, group, sub);   // -1 only if every remaining weight is 0
             if (draw && sub == j) my_pick = pick;
         }
     }

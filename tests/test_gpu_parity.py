@@ -714,3 +714,70 @@ def test_whole_step_replays_from_a_hip_graph():
         ids = want[1]["nbr"].ravel()
         assert node_out.cpu().numpy().tobytes() == oracle.gather(node_np, ids).tobytes()
         assert tuple(hit_miss.tolist()) == oracle.cache_hits(T.cache_residents(cache).numpy(), w.num_nodes, ids)
+
+
+def test_two_stream_step_replays_from_a_hip_graph():
+    """The same step with the lookup split over two streams, as the benchmark's pipelined schedule
+    issues it: the classification and the staging of missed rows on a side stream that is forked
+    from and joined to the capturing stream by events inside the capture, beside the edge gather;
+    the node gather after the join. Replayed with new roots; every replay equals the oracle."""
+    w = W.make(1)
+    g, g_ref = build_both(w.src, w.dst, w.ts, w.eid, w.num_nodes)
+    rng = np.random.default_rng(4)
+    node_np = rng.standard_normal((w.num_nodes, 413)).astype(np.float32)
+    node_host = torch.from_numpy(node_np).pin_memory()
+    cache = T.cache_init(node_host, 200, None, seed=6, staging_rows=800)
+    T.cache_tune(cache, stage_blocks=8, refresh_before_gather=True)
+    table = dev(w.edge_feat)
+    R, k = 600, 10
+    roots_d = torch.empty(R, dtype=torch.int32, device="cuda")
+    times_d = torch.empty(R, dtype=torch.int64, device="cuda")
+    hit_miss = torch.zeros(2, dtype=torch.int64, device="cuda")
+    ids = torch.empty(R + R * k + R * k * k, dtype=torch.int32, device="cuda")      # roots | hop-1 nodes | hop-2 nodes
+    out = [dict(nbr=ids[R:R + R * k], eid=torch.empty(R * k, dtype=torch.int32, device="cuda"),
+                ts=torch.empty(R * k, dtype=torch.int64, device="cuda"), count=torch.empty(R, dtype=torch.int32, device="cuda")),
+           dict(nbr=ids[R + R * k:], eid=torch.empty(R * k * k, dtype=torch.int32, device="cuda"),
+                ts=torch.empty(R * k * k, dtype=torch.int64, device="cuda"), count=torch.empty(R * k, dtype=torch.int32, device="cuda"))]
+    edge_out = torch.empty((R * k * k, w.edge_feat.shape[1]), dtype=torch.float32, device="cuda")
+    node_out = torch.empty((ids.numel(), 413), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    forked, joined = torch.cuda.Event(), torch.cuda.Event()
+
+    def step(main):
+        ids[:R].copy_(roots_d)
+        T.sample_temporal(g, roots_d, times_d, k, 2, T.RECENT, 11, out=out, stream=main)
+        forked.record(main)
+        side.wait_event(forked)
+        T.cache_prefetch(cache, ids, hit_miss=hit_miss, stream=side)
+        joined.record(side)
+        T.gather_features(table, out[1]["eid"], out=edge_out, stream=main)
+        main.wait_event(joined)
+        T.cache_gather(cache, ids, out=node_out, stream=main)
+
+    roots, times = w.batches[2]
+    roots_d.copy_(torch.from_numpy(roots))
+    times_d.copy_(torch.from_numpy(times))
+    step(torch.cuda.current_stream())                                 # warm-up: the handle's scratch has its final size
+    torch.cuda.synchronize()
+    capture = torch.cuda.Stream()
+    capture.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(capture):
+        with torch.cuda.graph(graph, stream=capture):
+            step(capture)
+    torch.cuda.current_stream().wait_stream(capture)
+    for b in (8, 1, 6):
+        roots, times = w.batches[b]
+        roots_d.copy_(torch.from_numpy(roots))                        # eager work between the replays
+        times_d.copy_(torch.from_numpy(times))
+        hit_miss.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = oracle.sample_temporal(g_ref, roots, times, k, 2, W.RECENT, 11, threads=THREADS)
+        for h in range(2):
+            for f in FIELDS:
+                assert np.array_equal(out[h][f].cpu().numpy().reshape(want[h][f].shape), want[h][f]), (b, h, f)
+        assert edge_out.cpu().numpy().tobytes() == oracle.gather(w.edge_feat, want[1]["eid"].ravel()).tobytes()
+        ids_np = np.concatenate([roots, want[0]["nbr"].ravel(), want[1]["nbr"].ravel()])
+        assert node_out.cpu().numpy().tobytes() == oracle.gather(node_np, ids_np).tobytes()
+        assert tuple(hit_miss.tolist()) == oracle.cache_hits(T.cache_residents(cache).numpy(), w.num_nodes, ids_np)
