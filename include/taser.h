@@ -243,10 +243,11 @@ int taser_gather_features(const void* table, int64_t rows, int32_t row_bytes,
  *                   shuffle of 0..rows-1 with draw j keyed (seed, hop tag
  *                   0x43414348, root index j, slot 0) ("randomly cache k
  *                   features", Alg. 3)
- *   staging_rows    rows of per-call device staging (>= 0): rows that miss are
- *                   fetched from host memory once per call into it, however
- *                   often the call requests them; requests that find it full
- *                   read host memory directly.
+ *   staging_rows    rows of per-call device staging (>= 0): the distinct rows
+ *                   that miss are fetched from host memory once per call into
+ *                   it (in consecutive rows, as many as fit), however often the
+ *                   call requests them; requests for further rows read host
+ *                   memory directly.
  * This call synchronizes `hip_stream` before returning.
  *
  * taser_cache_lookup serves n rows into the dense `out` exactly like

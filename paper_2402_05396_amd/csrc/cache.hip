@@ -13,13 +13,16 @@
 // A lookup is three kernels (1-2 = taser_cache_prefetch, 3 = taser_cache_gather;
 // split so that a caller can run the bus-bound part beside other work):
 //   1. classify: every request probes the resident hash; a miss claims a slot
-//      of the miss table (compare-and-swap on the id, the slot index doubles as
-//      the staging row) — the outcome per request is written to `loc`;
-//   2. stage: one wave per claimed slot copies that row host -> staging and
-//      empties the slot, so the miss table is clear again for the next call;
+//      of the miss table (compare-and-swap on the id) — the outcome per request
+//      is written to `loc`;
+//   2. stage: the claimed slots get consecutive rows of the staging area (so
+//      that what a call staged is one dense block of memory), a wave per slot
+//      copies that row host -> staging and empties the slot, so the miss table
+//      is clear again for the next call; a third small kernel rewrites the
+//      locations of the missed requests from table slot to staging row;
 //   3. gather: the dense output is written from cache rows / staged rows /
 //      zero rows, or straight from host memory for requests that found the
-//      miss table full.
+//      miss table or the staging area full.
 // Which rows are resident only changes where bytes come from, never the bytes.
 #include <cstdio>
 #include <mutex>
@@ -46,7 +49,8 @@ __host__ __device__ inline uint32_t hash_id(int32_t id, uint32_t mask) {
     h ^= h >> 15;
     return h & mask;
 }
-// loc encoding: >= 0 cache slot; kLocZero; kLocHost; otherwise -2 - staging slot
+// loc encoding: >= 0 cache slot; kLocZero; kLocHost; otherwise -2 - s, where s is a slot of the
+// miss table between classify and resolve, a row of the staging area afterwards
 __host__ __device__ inline int32_t loc_of_stage(uint32_t s) { return -2 - (int32_t)s; }
 
 }  // namespace
@@ -62,9 +66,12 @@ struct taser_cache {
     int32_t* hash_key;          // device [hash_size], kEmpty or a resident id
     int32_t* hash_slot;         // device [hash_size]
     uint32_t hash_mask;
-    uint8_t* stage_rows;        // device [miss_size][dev_pitch]
+    uint8_t* stage_rows;        // device [staging_rows][dev_pitch]
+    int64_t staging_rows;
     int32_t* miss_key;          // device [miss_size], all kEmpty between lookups
-    uint32_t miss_size;         // 0 or a power of two
+    int32_t* miss_row;          // device [miss_size]: staging row of a claimed slot (-1: the staging area was full)
+    uint32_t* stage_count;      // device [1]: staging rows handed out by the running call, 0 between calls
+    uint32_t miss_size;         // 0 or a power of two >= 2 * staging_rows
     int32_t* loc;               // device [loc_capacity], per-request outcome
     int64_t loc_capacity;
     const int32_t* prefetched_ids;   // what `loc` currently describes (set by taser_cache_prefetch)
@@ -218,7 +225,8 @@ __global__ __launch_bounds__(kThreads) void tally_kernel(const uint32_t* __restr
 // a wave reads 64 table slots at a time and walks the claimed ones.
 constexpr int kStageBlocks = 64;
 
-__global__ __launch_bounds__(kThreads) void stage_kernel(int32_t* __restrict__ miss_key, uint32_t miss_size,
+__global__ __launch_bounds__(kThreads) void stage_kernel(int32_t* __restrict__ miss_key, int32_t* __restrict__ miss_row,
+                                                         uint32_t miss_size, uint32_t* stage_count, uint32_t staging_rows,
                                                          const uint8_t* __restrict__ host_rows, int64_t pitch_bytes,
                                                          uint32_t row_dwords, uint8_t* __restrict__ stage_rows,
                                                          int32_t dev_pitch) {
@@ -231,12 +239,21 @@ __global__ __launch_bounds__(kThreads) void stage_kernel(int32_t* __restrict__ m
         const int32_t key = miss_key[base + lane];
         if (key >= 0) miss_key[base + lane] = kEmpty;   // the table is empty again for the next call's claims
         uint64_t claimed = __ballot(key >= 0);
+        if (!claimed) continue;
+        // consecutive staging rows for this wave's claimed slots: one atomic per 64 slots
+        uint32_t first = 0;
+        if (lane == 0) first = atomicAdd(stage_count, (uint32_t)__popcll(claimed));
+        first = __builtin_amdgcn_readfirstlane(first);
+        const uint32_t my_row = first + (uint32_t)__popcll(claimed & (((uint64_t)1 << lane) - 1));
+        if (key >= 0) miss_row[base + lane] = my_row < staging_rows ? (int32_t)my_row : -1;
         while (claimed) {
             const int l = __ffsll((long long)claimed) - 1;
             claimed &= claimed - 1;
+            const uint32_t row = __builtin_amdgcn_readlane(my_row, l);
+            if (row >= staging_rows) break;             // later lanes have later rows: nothing more fits
             const int32_t id = __builtin_amdgcn_readlane(key, l);
             const uint8_t* from = host_rows + (int64_t)id * pitch_bytes;
-            uint8_t* to = stage_rows + (int64_t)(base + l) * dev_pitch;
+            uint8_t* to = stage_rows + (int64_t)row * dev_pitch;
             // 16-byte pieces (4-byte aligned on both sides), two per lane in flight
             for (uint32_t c = lane; c < chunks; c += 2 * kWave) {
                 const uint32_t c2 = c + kWave;
@@ -248,6 +265,21 @@ __global__ __launch_bounds__(kThreads) void stage_kernel(int32_t* __restrict__ m
             }
             if (lane < tail)
                 reinterpret_cast<uint32_t*>(to)[chunks * 4u + lane] = reinterpret_cast<const uint32_t*>(from)[chunks * 4u + lane];
+        }
+    }
+}
+
+// After the staging: the location of a missed request changes from its miss-table slot to the
+// staging row that slot was given (or to "read host memory" when the staging area was full),
+// and the row counter goes back to zero for the next call.
+__global__ __launch_bounds__(kThreads) void resolve_kernel(int32_t* __restrict__ loc, int64_t n,
+                                                           const int32_t* __restrict__ miss_row, uint32_t* stage_count) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *stage_count = 0;   // the stage kernel before this one has finished
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kThreads) {
+        const int32_t where = loc[i];
+        if (where < kLocZero && where != kLocHost) {
+            const int32_t row = miss_row[-2 - where];
+            loc[i] = row >= 0 ? loc_of_stage((uint32_t)row) : kLocHost;
         }
     }
 }
@@ -267,13 +299,23 @@ struct RewriteJob {
 
 __global__ __launch_bounds__(kThreads) void rewrite_kernel(RewriteJob job, uint32_t zero) {
     using taser_gather::u32x4;
+    constexpr int kPer = 4;   // 16-byte pieces per thread and round: their loads are issued together
     for (int a = 0; a < 3; ++a) {
         u32x4* quads = reinterpret_cast<u32x4*>(job.words[a]);   // bases are allocation starts: 16-byte aligned
         const int64_t nq = job.count[a] / 4;
-        for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nq; i += (int64_t)gridDim.x * kThreads) {
-            u32x4 v = quads[i];
-            v.x ^= zero;
-            quads[i] = v;
+        for (int64_t i0 = (int64_t)blockIdx.x * (kThreads * kPer) + threadIdx.x; i0 < nq; i0 += (int64_t)gridDim.x * (kThreads * kPer)) {
+            u32x4 v[kPer];
+#pragma unroll
+            for (int u = 0; u < kPer; ++u) {
+                const int64_t i = i0 + u * kThreads;
+                v[u] = quads[i < nq ? i : nq - 1];
+            }
+#pragma unroll
+            for (int u = 0; u < kPer; ++u) {
+                const int64_t i = i0 + u * kThreads;
+                v[u].x ^= zero;
+                if (i < nq) quads[i] = v[u];
+            }
         }
         const int64_t t = nq * 4 + (int64_t)blockIdx.x * kThreads + threadIdx.x;
         if (t < job.count[a]) job.words[a][t] ^= zero;
@@ -376,7 +418,7 @@ uint32_t pow2_at_least(uint64_t x) {
 
 void destroy(taser_cache* c) {
     if (!c) return;
-    void* const owned[] = {c->cache_rows, c->hash_key, c->hash_slot, c->stage_rows, c->miss_key,
+    void* const owned[] = {c->cache_rows, c->hash_key, c->hash_slot, c->stage_rows, c->miss_key, c->miss_row, c->stage_count,
                            c->loc, c->resident_dev, c->access_count, c->block_tally, c->epoch_hist, c->epoch_rank,
                            c->epoch_pos, c->epoch_partial, c->epoch_selected, c->epoch_overlap};
     int at = 0;
@@ -530,6 +572,7 @@ extern "C" int taser_cache_init(const void* host_table, int64_t rows, int32_t ro
 
     const uint32_t hash_size = pow2_at_least((uint64_t)(capacity_rows > 8 ? capacity_rows : 8) * 2);
     c->hash_mask = hash_size - 1;
+    c->staging_rows = staging_rows;
     c->miss_size = staging_rows > 0 ? pow2_at_least((uint64_t)(staging_rows > 32 ? staging_rows : 32) * 2) : 0;   // >= 64
 
 #define CACHE_TRY(expr)                                               \
@@ -543,10 +586,13 @@ extern "C" int taser_cache_init(const void* host_table, int64_t rows, int32_t ro
     CACHE_TRY(hipMalloc((void**)&c->resident_dev, (size_t)(capacity_rows > 0 ? capacity_rows : 1) * sizeof(int32_t)));
     CACHE_TRY(hipMalloc((void**)&c->block_tally, (size_t)2 * kClassifyBlocks * sizeof(uint32_t)));
     if (c->miss_size) {
-        CACHE_TRY(hipMalloc((void**)&c->stage_rows, (size_t)c->miss_size * c->dev_pitch));
+        CACHE_TRY(hipMalloc((void**)&c->stage_rows, (size_t)staging_rows * c->dev_pitch));
         CACHE_TRY(hipMalloc((void**)&c->miss_key, (size_t)c->miss_size * sizeof(int32_t)));
+        CACHE_TRY(hipMalloc((void**)&c->miss_row, (size_t)c->miss_size * sizeof(int32_t)));
+        CACHE_TRY(hipMalloc((void**)&c->stage_count, sizeof(uint32_t)));
         hipLaunchKernelGGL(fill_kernel, dim3((c->miss_size + kThreads - 1) / kThreads), dim3(kThreads), 0, stream,
                            c->miss_key, c->miss_size, kEmpty);
+        hipLaunchKernelGGL(fill_kernel, dim3(1), dim3(kThreads), 0, stream, reinterpret_cast<int32_t*>(c->stage_count), 1u, 0);
     }
 #undef CACHE_TRY
     const int rc = install_residents(c, stream);
@@ -572,8 +618,10 @@ static int enqueue_prefetch(taser_cache* c, const int32_t* ids, int64_t n, uint6
     }
     if (c->miss_size) {
         TaserProfileSpan span(stream, "cache_stage_misses");
-        hipLaunchKernelGGL(stage_kernel, dim3(c->stage_blocks), dim3(kThreads), 0, stream, c->miss_key, c->miss_size,
-                           c->host_rows, c->pitch_bytes, (uint32_t)c->row_bytes / 4u, c->stage_rows, c->dev_pitch);
+        hipLaunchKernelGGL(stage_kernel, dim3(c->stage_blocks), dim3(kThreads), 0, stream, c->miss_key, c->miss_row,
+                           c->miss_size, c->stage_count, (uint32_t)c->staging_rows, c->host_rows, c->pitch_bytes,
+                           (uint32_t)c->row_bytes / 4u, c->stage_rows, c->dev_pitch);
+        hipLaunchKernelGGL(resolve_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, loc, n, c->miss_row, c->stage_count);
     }
     TASER_HIP_TRY(hipGetLastError());
     return TASER_OK;
@@ -591,7 +639,7 @@ static int enqueue_gather(taser_cache* c, const int32_t* ids, int64_t n, void* o
         job.words[1] = reinterpret_cast<uint32_t*>(c->cache_rows);
         job.count[1] = c->capacity * (int64_t)c->dev_pitch / 4;
         job.words[2] = reinterpret_cast<uint32_t*>(c->stage_rows);
-        job.count[2] = (int64_t)c->miss_size * c->dev_pitch / 4;
+        job.count[2] = c->miss_size ? c->staging_rows * (int64_t)c->dev_pitch / 4 : 0;
         TaserProfileSpan span(stream, "cache_refresh_working_set");
         hipLaunchKernelGGL(rewrite_kernel, dim3(2048), dim3(kThreads), 0, stream, job, 0u);
     }
