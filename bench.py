@@ -26,9 +26,9 @@ EDGE_PITCH_ELEMS = {186: 192}   # rows padded to whole 128-byte lines where the 
 # (FETCH_SIZE, then WRITE_SIZE). The counters cannot be read from inside this process, so
 # the figure is a constant taken from the named summary, not from the run that prints it.
 MEASURED_TRAFFIC = {
-    # (2 x 339 098.5 + 2 149 574.4) KiB per launch
+    # (2 x 341 777.4 + 2 149 514.6) KiB per launch
     ("C5-gdelt-shaped", "cache_gather_rows"): (
-        2895638000, "profiles/c5_gdelt_shaped_hbm_traffic_pmc.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this "
+        2901063066, "profiles/c5_gdelt_shaped_hbm_traffic_pmc.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this "
                     "benchmark with --edges 20000000 (the node gather reads the same 17 000-row table and serves "
                     "the same number of requests at any event count); not measured in this run"),
 }
