@@ -26,9 +26,9 @@ EDGE_PITCH_ELEMS = {186: 192}   # rows padded to whole 128-byte lines where the 
 # (FETCH_SIZE, then WRITE_SIZE). The counters cannot be read from inside this process, so
 # the figure is a constant taken from the named summary, not from the run that prints it.
 MEASURED_TRAFFIC = {
-    # (2 x 341 777.4 + 2 149 514.6) KiB per launch
+    # (2 x 136 752.8 + 2 148 911.8) KiB per launch
     ("C5-gdelt-shaped", "cache_gather_rows"): (
-        2901063066, "profiles/c5_gdelt_shaped_hbm_traffic_pmc.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this "
+        2480555418, "profiles/c5_gdelt_shaped_hbm_traffic_pmc.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this "
                     "benchmark with --edges 20000000 (the node gather reads the same 17 000-row table and serves "
                     "the same number of requests at any event count); not measured in this run"),
 }
@@ -55,6 +55,7 @@ def main():
                          "one HIP graph and time its replay (the roofline kernel's time then comes from the second, "
                          "eager pass)")
     ap.add_argument("--no-refresh", action="store_true", help="do not re-write the gather's working set before the node gather")
+    ap.add_argument("--flat-gather", action="store_true", help="node gather in plain output order instead of by L2 partition")
     ap.add_argument("--cache-ratio", type=float, default=None,
                     help="override the share of node rows resident in the device cache (then it is not the named workload)")
     ap.add_argument("--cpu-roots", type=int, default=6000, help="roots of batch 0 the CPU oracle is timed on (0 = skip)")
@@ -152,20 +153,28 @@ def main():
     if cache is not None:
         # One counted pass over all batches with the random content (sampling + classification only),
         # then the epoch end replaces it by the most requested rows.
-        hm0 = torch.zeros(2, dtype=torch.int64, device=dev)
-        T.cache_count_accesses(cache)
-        for b in batches:
-            T.sample_temporal(g, b["roots"], b["times"], k, hops, policy, 42, w.m, weight, out=b["out"])
-            T.cache_prefetch(cache, b["ids"], hit_miss=hm0)
-        replaced, overlap = T.cache_epoch_end(cache, min_overlap=cap)
-        T.cache_count_accesses(cache, False)
-        h0, m0 = hm0.tolist()
+        def counted_epoch(c):
+            hm0 = torch.zeros(2, dtype=torch.int64, device=dev)
+            T.cache_count_accesses(c)
+            for b in batches:
+                T.sample_temporal(g, b["roots"], b["times"], k, hops, policy, 42, w.m, weight, out=b["out"])
+                T.cache_prefetch(c, b["ids"], hit_miss=hm0)
+            replaced, overlap = T.cache_epoch_end(c, min_overlap=cap)
+            T.cache_count_accesses(c, False)
+            return hm0.tolist(), replaced, overlap
+        (h0, m0), replaced, overlap = counted_epoch(cache)
         residents = T.cache_residents(cache)
         warmup_epoch = {"batches": len(batches), "hit_rate_random_residents": round(h0 / max(h0 + m0, 1), 4),
                         "top_rows_resident_before": overlap, "replaced": replaced}
         log(f"cache warm-up epoch: hit rate {warmup_epoch['hit_rate_random_residents']} with random residents, "
             f"{overlap} of the {cap} most requested rows were resident, replaced = {replaced}")
+        # the second handle: the same content, and one counted epoch of its own (the epoch end also
+        # records which rows are requested most, which the gather uses to balance its work)
         caches.append(T.cache_init(node_host, cap, residents, staging_rows=w.num_nodes - cap))
+        _, replaced2, _ = counted_epoch(caches[1])
+        assert not replaced2 and torch.equal(T.cache_residents(caches[1]), residents)
+        for c in caches:
+            T.cache_tune(c, partitioned_gather=not args.flat_gather)
         if args.schedule != "serial":
             for c in caches:
                 T.cache_tune(c, stage_blocks=args.stage_blocks, refresh_before_gather=not args.no_refresh)

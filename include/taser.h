@@ -300,7 +300,7 @@ int taser_cache_gather(taser_cache* c, const int32_t* ids, int64_t n, void* out,
 int taser_cache_lookup_static(taser_cache* c, const int32_t* ids, int64_t n, void* out,
                               uint64_t* hit_miss, void* hip_stream);
 
-/* Two knobs for callers that run the halves of a lookup beside other kernels.
+/* Knobs for callers that run the halves of a lookup beside other kernels, and for measurements.
  *   stage_blocks  number of 256-thread blocks the host -> staging copy runs on
  *                 (default 64; 0 keeps the current value). The copy is bound by
  *                 the bus; fewer blocks copy somewhat slower but leave more of
@@ -310,8 +310,21 @@ int taser_cache_lookup_static(taser_cache* c, const int32_t* ids, int64_t n, voi
  *                 place. Worth it only when other bandwidth-heavy kernels run
  *                 between prefetch and gather (they push that working set out of
  *                 the memory-side cache, which does not take it back on reads).
- *                 Default off. Never changes results. */
-int taser_cache_tune(taser_cache* c, int32_t stage_blocks, int32_t refresh_before_gather);
+ *                 Default off. Never changes results.
+ *   partitioned_gather  negative keeps the current setting. 1 (the default): a
+ *                 lookup of at least 4096 rows of 512 bytes to 16 KiB hands out
+ *                 its output in 128-byte lines, each to a workgroup on the L2
+ *                 partition of the chip that serves the line's source row, so
+ *                 that a row is read from memory through one partition rather
+ *                 than through all eight (a table of a few tens of MB is then
+ *                 fetched about once per lookup). Rows that taser_cache_epoch_end
+ *                 found to draw at least 1/4096 of all requests are spread by
+ *                 request position instead (they sit in every L2 anyway, and the
+ *                 partitions' loads stay equal). 0: always the plain gather in
+ *                 output order. 2: the partitioned kernel with every row spread
+ *                 by position (for measurements). Never changes results. */
+int taser_cache_tune(taser_cache* c, int32_t stage_blocks, int32_t refresh_before_gather,
+                     int32_t partitioned_gather);
 
 /* ---------------------------------------------------------------------------
  * Cache maintenance (Alg. 3; Sec. 3.4): count how often every row is requested
@@ -333,7 +346,9 @@ int taser_cache_tune(taser_cache* c, int32_t stage_blocks, int32_t refresh_befor
  * many of them are resident. If that is below min_overlap the cache content is
  * replaced by Q_topk (slots in ascending id order: rows re-read from the host
  * table, index rebuilt) and *replaced (host, may be NULL) is set to 1, else 0.
- * The counters are zeroed either way. Synchronizes `hip_stream`; no lookup on
+ * Either way the resident rows that drew at least 1/4096 of the epoch's requests
+ * are noted (see partitioned_gather above; nothing else uses the note) and the
+ * counters are zeroed. Synchronizes `hip_stream`; no lookup on
  * this handle may be in flight. TASER_E_ARG if counting was never enabled.
  * ------------------------------------------------------------------------- */
 int taser_cache_count_accesses(taser_cache* c, int32_t enable, void* hip_stream);

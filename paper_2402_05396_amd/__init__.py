@@ -68,7 +68,7 @@ def lib():
         L.taser_cache_lookup_static.argtypes = [vp, vp, i64, vp, vp, vp]
         L.taser_cache_prefetch.argtypes = [vp, vp, i64, vp, vp]
         L.taser_cache_gather.argtypes = [vp, vp, i64, vp, vp]
-        L.taser_cache_tune.argtypes = [vp, i32, i32]
+        L.taser_cache_tune.argtypes = [vp, i32, i32, i32]
         L.taser_cache_count_accesses.argtypes = [vp, i32, vp]
         L.taser_cache_access_counts.argtypes = [vp, vp, vp]
         L.taser_cache_epoch_end.argtypes = [vp, i64, ctypes.POINTER(i64), ctypes.POINTER(i32), vp]
@@ -349,9 +349,10 @@ def cache_gather(c, ids, out=None, stream=None):
     return out
 
 
-def cache_tune(c, stage_blocks=0, refresh_before_gather=False):
-    """taser_cache_tune."""
-    _check(lib().taser_cache_tune(c.handle, stage_blocks, 1 if refresh_before_gather else 0))
+def cache_tune(c, stage_blocks=0, refresh_before_gather=False, partitioned_gather=None):
+    """taser_cache_tune (partitioned_gather None keeps the current setting)."""
+    _check(lib().taser_cache_tune(c.handle, stage_blocks, 1 if refresh_before_gather else 0,
+                                  -1 if partitioned_gather is None else int(partitioned_gather)))
 
 
 def cache_count_accesses(c, enable=True, stream=None):

@@ -43,13 +43,17 @@ constexpr int kMaxMissProbes = 128;
 constexpr int kTallySlots = 1024;                 // per-block LDS table of the access counting
 constexpr uint32_t kTagCache = 0x43414348u;        // hop tag of the residency shuffle
 constexpr int kClassifyBlocks = 2048;             // grid-stride: 8 blocks per compute unit
+constexpr int32_t kHotBit = 1 << 30;               // in a cache-slot location: a row that drew a large share of the
+                                                   // last epoch's requests (see mark_hot_kernel)
+constexpr int32_t kSlotMask = kHotBit - 1;
+constexpr uint64_t kHotShare = 4096;               // hot = at least 1/4096 of all counted requests
 
 __host__ __device__ inline uint32_t hash_id(int32_t id, uint32_t mask) {
     uint32_t h = (uint32_t)id * 0x9E3779B1u;
     h ^= h >> 15;
     return h & mask;
 }
-// loc encoding: >= 0 cache slot; kLocZero; kLocHost; otherwise -2 - s, where s is a slot of the
+// loc encoding: >= 0 cache slot (| kHotBit); kLocZero; kLocHost; otherwise -2 - s, where s is a slot of the
 // miss table between classify and resolve, a row of the staging area afterwards
 __host__ __device__ inline int32_t loc_of_stage(uint32_t s) { return -2 - (int32_t)s; }
 
@@ -78,6 +82,7 @@ struct taser_cache {
     int64_t prefetched_n;
     int stage_blocks;                // width of the host -> staging copy, in 256-thread blocks
     bool refresh_before_gather;      // see rewrite_kernel
+    int partitioned_gather;          // gather through gather_owned_lines_kernel where it applies (0 off, 1 on, 2: owners by position only, for measurements)
     std::vector<int32_t>* residents;   // host copy, slot order
     int32_t* resident_dev;             // device copy of the same
     uint32_t* access_count;            // device [rows] or null: requests per row since the last epoch end
@@ -330,14 +335,27 @@ struct CacheSource {
     int32_t dev_pitch;
     const uint8_t* host_rows;
     int64_t pitch_bytes;
+    int owner_mode;   // 1: by source row; 2: by position only
     __device__ __forceinline__ int32_t key(int64_t i) const { return loc[i]; }
     __device__ __forceinline__ const uint8_t* address(int32_t where, int64_t i) const {
         // cache row or staged row: one multiply-add either way, no branch
         const bool cached = where >= 0;
-        const uint8_t* at = (cached ? cache_rows : stage_rows) + (int64_t)(cached ? where : -2 - where) * dev_pitch;
+        const uint8_t* at = (cached ? cache_rows : stage_rows) + (int64_t)(cached ? (where & kSlotMask) : -2 - where) * dev_pitch;
         if (where == kLocZero) at = nullptr;
         if (__builtin_expect(where == kLocHost, 0)) at = host_rows + (int64_t)ids[i] * pitch_bytes;
         return at;
+    }
+    // Which L2 partition serves request i (see gather_owned_lines_kernel): chosen by the source row,
+    // so that a row is read through one partition only; by the request's position for zero rows,
+    // rows read from host memory and hot rows (a handful of rows that a large part of all requests
+    // name: they stay in every partition's L2 anyway, and tying each to one partition would give
+    // that partition several times the others' work).
+    __device__ __forceinline__ uint32_t owner(int32_t where, int64_t i) const {
+        uint32_t v = (uint32_t)i;
+        if (owner_mode == 2) return v % taser_gather::kOwnerClasses;
+        if (where >= 0 && !(where & kHotBit)) v = ((uint32_t)where * 0x9E3779B1u) >> 20;
+        else if (where < kLocZero && where != kLocHost) v = ((uint32_t)(-2 - where) * 0x9E3779B1u) >> 19;
+        return v % taser_gather::kOwnerClasses;
     }
 };
 
@@ -394,6 +412,30 @@ __global__ __launch_bounds__(kThreads) void emit_selected_kernel(const uint32_t*
     }
     const unsigned long long both = __ballot(resident);
     if ((threadIdx.x & (kWave - 1)) == 0 && both) atomicAdd(overlap, (unsigned long long)__popcll(both));
+}
+
+// Sum of all access counters, added to *total.
+__global__ __launch_bounds__(kThreads) void sum_counts_kernel(const uint32_t* __restrict__ count, int64_t rows,
+                                                              unsigned long long* total) {
+    unsigned long long s = 0;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < rows; i += (int64_t)gridDim.x * kThreads) s += count[i];
+    for (int d = kWave / 2; d > 0; d >>= 1) s += __shfl_down(s, d, kWave);
+    if ((threadIdx.x & (kWave - 1)) == 0 && s) atomicAdd(total, s);
+}
+
+// Marks, in the id -> slot index, the resident rows that drew at least 1/kHotShare of the epoch's
+// counted requests (at most kHotShare rows can). Only the gather's choice of which L2 partition
+// serves a request looks at the mark.
+__global__ __launch_bounds__(kThreads) void mark_hot_kernel(const int32_t* __restrict__ hash_key, int32_t* __restrict__ hash_slot,
+                                                            uint32_t hash_size, const uint32_t* __restrict__ count,
+                                                            const unsigned long long* __restrict__ total, unsigned long long share) {
+    const uint32_t h = blockIdx.x * kThreads + threadIdx.x;
+    if (h >= hash_size) return;
+    const int32_t id = hash_key[h];
+    if (id == kEmpty) return;
+    const unsigned long long all = *total;
+    const bool hot = all > 0 && (unsigned long long)count[id] * share >= all;
+    hash_slot[h] = (hash_slot[h] & kSlotMask) | (hot ? kHotBit : 0);
 }
 
 // Philox4x32-10 on the host, for the default residency draw only.
@@ -506,6 +548,7 @@ extern "C" int taser_cache_init(const void* host_table, int64_t rows, int32_t ro
     if (row_bytes <= 0 || (row_bytes & 3)) return taser_fail(TASER_E_ARG, "cache_init: row_bytes = %d must be a positive multiple of 4", row_bytes);
     if (pitch_bytes < row_bytes || (pitch_bytes & 3)) return taser_fail(TASER_E_ARG, "cache_init: pitch_bytes = %lld must be a multiple of 4 and >= row_bytes", (long long)pitch_bytes);
     if (capacity_rows < 0 || capacity_rows > rows) return taser_fail(TASER_E_RANGE, "cache_init: capacity_rows = %lld outside [0, rows]", (long long)capacity_rows);
+    if (capacity_rows >= kHotBit) return taser_fail(TASER_E_RANGE, "cache_init: capacity_rows = %lld must stay below 2^30", (long long)capacity_rows);
     if (staging_rows < 0 || staging_rows > ((int64_t)1 << 29)) return taser_fail(TASER_E_RANGE, "cache_init: staging_rows = %lld outside [0, 2^29]", (long long)staging_rows);
     if ((uintptr_t)host_table & 3) return taser_fail(TASER_E_ARG, "cache_init: host table must be 4-byte aligned");
 
@@ -534,6 +577,7 @@ extern "C" int taser_cache_init(const void* host_table, int64_t rows, int32_t ro
     c->dev_pitch = row_bytes;
     c->stage_blocks = kStageBlocks;
     c->refresh_before_gather = false;
+    c->partitioned_gather = 1;
     c->residents = new (std::nothrow) std::vector<int32_t>();
     if (!c->residents) { destroy(c); return taser_fail(TASER_E_OOM, "cache_init: host allocation failed"); }
 
@@ -629,7 +673,7 @@ static int enqueue_prefetch(taser_cache* c, const int32_t* ids, int64_t n, uint6
 
 // The second half: the dense output from the locations in `loc`.
 static int enqueue_gather(taser_cache* c, const int32_t* ids, int64_t n, void* out, hipStream_t stream, int32_t* loc) {
-    const CacheSource source{loc, ids, c->cache_rows, c->stage_rows, c->dev_pitch, c->host_rows, c->pitch_bytes};
+    const CacheSource source{loc, ids, c->cache_rows, c->stage_rows, c->dev_pitch, c->host_rows, c->pitch_bytes, c->partitioned_gather};
     const int align = taser_gather::common_alignment((uint64_t)c->row_bytes | (uint64_t)c->pitch_bytes |
                                                      (uint64_t)(uintptr_t)c->host_rows);
     if (c->refresh_before_gather) {
@@ -644,7 +688,9 @@ static int enqueue_gather(taser_cache* c, const int32_t* ids, int64_t n, void* o
         hipLaunchKernelGGL(rewrite_kernel, dim3(2048), dim3(kThreads), 0, stream, job, 0u);
     }
     TaserProfileSpan span(stream, "cache_gather_rows");
-    if (!taser_gather::launch(source, align, c->row_bytes, n, out, stream))
+    const bool launched = c->partitioned_gather ? taser_gather::launch_owned(source, align, c->row_bytes, n, out, stream)
+                                                : taser_gather::launch(source, align, c->row_bytes, n, out, stream);
+    if (!launched)
         return taser_fail(TASER_E_RANGE, "cache_gather: %lld rows of %d bytes exceed one launch", (long long)n, c->row_bytes);
     TASER_HIP_TRY(hipGetLastError());
     return TASER_OK;
@@ -815,6 +861,12 @@ extern "C" int taser_cache_epoch_end(taser_cache* c, int64_t min_overlap, int64_
             c->prefetched_n = 0;
         }
     }
+    // which of the (new) residents were hot this epoch, then the counters start again
+    hipLaunchKernelGGL(fill_kernel, dim3(1), dim3(kThreads), 0, stream, reinterpret_cast<int32_t*>(c->epoch_overlap), 4u, 0);
+    hipLaunchKernelGGL(sum_counts_kernel, dim3(row_blocks < 256 ? row_blocks : 256), dim3(kThreads), 0, stream, c->access_count,
+                       rows, c->epoch_overlap + 1);
+    hipLaunchKernelGGL(mark_hot_kernel, dim3((c->hash_mask + kThreads) / kThreads), dim3(kThreads), 0, stream, c->hash_key,
+                       c->hash_slot, c->hash_mask + 1, c->access_count, c->epoch_overlap + 1, (unsigned long long)kHotShare);
     hipLaunchKernelGGL(fill_kernel, dim3(row_blocks), dim3(kThreads), 0, stream, reinterpret_cast<int32_t*>(c->access_count),
                        (uint32_t)rows, 0);
     TASER_HIP_TRY(hipGetLastError());
@@ -824,11 +876,13 @@ extern "C" int taser_cache_epoch_end(taser_cache* c, int64_t min_overlap, int64_
     return TASER_OK;
 }
 
-extern "C" int taser_cache_tune(taser_cache* c, int32_t stage_blocks, int32_t refresh_before_gather) {
+extern "C" int taser_cache_tune(taser_cache* c, int32_t stage_blocks, int32_t refresh_before_gather,
+                                int32_t partitioned_gather) {
     if (!c) return taser_fail(TASER_E_ARG, "cache_tune: null cache");
     if (stage_blocks < 0 || stage_blocks > 4096) return taser_fail(TASER_E_RANGE, "cache_tune: stage_blocks = %d outside [0, 4096]", stage_blocks);
     if (stage_blocks > 0) c->stage_blocks = stage_blocks;
     c->refresh_before_gather = refresh_before_gather != 0;
+    if (partitioned_gather >= 0) c->partitioned_gather = partitioned_gather > 2 ? 1 : partitioned_gather;
     return TASER_OK;
 }
 

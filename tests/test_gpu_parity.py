@@ -489,6 +489,33 @@ def test_cache_serves_identical_bytes_whatever_is_resident(cap_frac, staging):
         T.cache_free(c)
 
 
+@pytest.mark.parametrize("dim,n", [(128, 5000), (129, 4099), (413, 70001), (1025, 4097), (4096, 4096), (4095, 4100), (127, 9000)])
+def test_cache_partitioned_gather_equals_the_oracle(dim, n):
+    """The gather that hands the output out in 128-byte lines by source row (rows of 512 bytes and
+    more), before and after an epoch end has marked the most requested rows, and with every row
+    spread by position: same bytes as the oracle, and as the plain gather in output order."""
+    rng = np.random.default_rng(dim * 7 + n)
+    rows = 900
+    host = torch.from_numpy(rng.standard_normal((rows, dim)).astype(np.float32)).pin_memory()
+    cap = 300
+    c = T.cache_init(host, cap, torch.from_numpy(rng.permutation(rows)[:cap].astype(np.int32)), staging_rows=200)
+    T.cache_count_accesses(c)
+    for epoch in range(2):
+        ids_np = np.minimum(rng.zipf(1.1, n) - 1, rows - 1).astype(np.int32)
+        ids_np[::41] = -1
+        ids_np[5::577] = rows                                        # out of range: a zero row
+        ids_np[-3:] = [-1, 7, -1]                                    # zero rows around the ragged end
+        ids = dev(ids_np)
+        want = oracle.gather(host.numpy(), np.where(ids_np >= rows, -1, ids_np), threads=THREADS).tobytes()
+        for mode in (1, 0, 2):
+            T.cache_tune(c, partitioned_gather=mode)
+            out = torch.full((n, dim), float("nan"), dtype=torch.float32, device="cuda")
+            T.cache_lookup(c, ids, out=out)
+            torch.cuda.synchronize()
+            assert out.cpu().numpy().tobytes() == want, (epoch, mode)
+        T.cache_epoch_end(c, min_overlap=cap if epoch == 0 else 0)     # marks hot rows (and swaps the content once)
+
+
 def test_cache_rejects_unpinned_and_bad_residents():
     host = torch.zeros((100, 8), dtype=torch.float32)
     with pytest.raises(T.TaserError) as e:

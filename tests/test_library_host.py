@@ -103,7 +103,7 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert "exceeds" in T.last_error()
     assert lib.taser_cache_prefetch(None, one, 1, None, None) == E_ARG
     assert lib.taser_cache_gather(None, one, 1, one, None) == E_ARG
-    assert lib.taser_cache_tune(None, 1, 0) == E_ARG
+    assert lib.taser_cache_tune(None, 1, 0, -1) == E_ARG
     assert lib.taser_cache_count_accesses(None, 1, None) == E_ARG
     assert lib.taser_cache_access_counts(None, one, None) == E_ARG
     assert lib.taser_cache_epoch_end(None, 1, None, None, None) == E_ARG
