@@ -42,41 +42,50 @@ namespace {
 // group; every lane of the wave must call this.
 // R independent lists per group are searched side by side (their loads of a level are
 // issued together): the kernel is bound by how many dependent reads are in flight.
+// Positions are 32-bit: a graph has fewer than 2^31 entries, and the last position an index entry
+// stands for, ((i + 1) << 4 L) - 1 with i < ceil(n / 16^L), stays below n + 16^L < 2^32.
 template <int G, int R>
 __device__ __forceinline__ void group_cutoff(const TaserRec* __restrict__ rec, const TaserTimeIndex& index,
-                                             const int64_t (&lo)[R], const int64_t (&hi)[R], const int64_t (&t)[R],
-                                             int group, int sub, int64_t (&cnt)[R]) {
+                                             const uint32_t (&lo)[R], const uint32_t (&hi)[R], const int64_t (&t)[R],
+                                             int group, int sub, uint32_t (&cnt)[R]) {
+    const uint32_t n = (uint32_t)index.num_entries;
     int top[R];
-    int64_t at[R];   // entry of the current level that holds p*
+    uint32_t at[R];   // entry of the current level that holds p*
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        top[r] = 0;
-        while (top[r] < kTimeIndexLevels && ((hi[r] >> (4 * top[r])) - (lo[r] >> (4 * top[r]))) > 15) ++top[r];
+        // lowest level at which the list touches at most 16 entries: (hi >> 4 L) - (lo >> 4 L) is
+        // floor((hi - lo) / 16^L) or one more, so it is the first L with hi - lo < 16^(L + 1), or the next
+        const uint32_t d = hi[r] - lo[r];
+        const int bits = d ? 32 - __clz((int)d) : 0;
+        int L = bits ? (bits + 3) / 4 - 1 : 0;                          // <= 7 for d < 2^31
+        if ((hi[r] >> (4 * L)) - (lo[r] >> (4 * L)) > 15u) ++L;         // never beyond 7: positions below 2^31 differ by < 8 there
+        top[r] = L;
         at[r] = 0;
     }
+#pragma unroll
     for (int L = kTimeIndexLevels; L >= 0; --L) {
         bool any = false;
 #pragma unroll
         for (int r = 0; r < R; ++r) any |= L <= top[r];
         if (!__ballot(any)) continue;   // no list of this wave is at this level yet
-        const int64_t len = L == 0 ? index.num_entries : index.len[L - 1];
-        int64_t first[R], probe[R];
+        const uint32_t len = L == 0 ? n : (uint32_t)index.len[L - 1];
+        uint32_t first[R], probe[R];
         bool known_before[R], read[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {   // what to read
             const bool active = L <= top[r];
-            first[r] = at[r] * 16;
-            int width = 16;
+            first[r] = at[r] * 16u;
+            uint32_t width = 16;
             if (L == top[r]) {
                 first[r] = lo[r] >> (4 * L);
-                width = (int)((hi[r] >> (4 * L)) - first[r]) + 1;
+                width = (hi[r] >> (4 * L)) - first[r] + 1u;
             }
             known_before[r] = false;
             read[r] = false;
-            probe[r] = first[r] + sub;
-            if (active && sub < width && probe[r] < len) {
-                int64_t pos = ((probe[r] + 1) << (4 * L)) - 1;           // last position the entry stands for
-                if (pos >= index.num_entries) pos = index.num_entries - 1;
+            probe[r] = first[r] + (uint32_t)sub;
+            if (active && (uint32_t)sub < width && probe[r] < len) {
+                uint32_t pos = ((probe[r] + 1u) << (4 * L)) - 1u;       // last position the entry stands for
+                if (pos >= n) pos = n - 1u;
                 if (pos < lo[r]) known_before[r] = true;
                 else if (pos < hi[r]) read[r] = true;
                 if (L == 0) probe[r] = pos;
@@ -91,7 +100,7 @@ __device__ __forceinline__ void group_cutoff(const TaserRec* __restrict__ rec, c
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const bool before = known_before[r] || (read[r] && ts[r] < t[r]);
-            const int c = __popcll(group_bits<G>(__ballot(before), group));   // before is monotone in the lane
+            const uint32_t c = (uint32_t)__popcll(group_bits<G>(__ballot(before), group));   // before is monotone in the lane
             if (L <= top[r]) at[r] = first[r] + c;
         }
     }
@@ -103,10 +112,11 @@ __device__ __forceinline__ void group_cutoff(const TaserRec* __restrict__ rec, c
 template <int G>
 __device__ __forceinline__ int64_t group_cutoff(const TaserRec* __restrict__ rec, const TaserTimeIndex& index,
                                                 int64_t lo, int64_t hi, int64_t t, int group, int sub) {
-    const int64_t lo1[1] = {lo}, hi1[1] = {hi}, t1[1] = {t};
-    int64_t cnt1[1];
+    const uint32_t lo1[1] = {(uint32_t)lo}, hi1[1] = {(uint32_t)hi};
+    const int64_t t1[1] = {t};
+    uint32_t cnt1[1];
     group_cutoff<G, 1>(rec, index, lo1, hi1, t1, group, sub, cnt1);
-    return cnt1[0];
+    return (int64_t)cnt1[0];
 }
 
 __device__ __forceinline__ void store_slot(int32_t* o_nbr, int32_t* o_eid, int64_t* o_ts,
@@ -118,88 +128,123 @@ __device__ __forceinline__ void store_slot(int32_t* o_nbr, int32_t* o_eid, int64
 
 constexpr int kThreads = 256;
 
-// Selection for one root whose cutoff is known. Returns, in lane `sub` of the root's group, the
-// record of output slot `sub` (padding from slot `filled` on); every lane of the wave must call it.
-template <int POLICY, int G>
-__device__ __forceinline__ TaserRec select_slot(
-    const TaserRec* __restrict__ rec, int64_t q, int64_t lo, int64_t cnt, int group, int sub, int k,
-    uint32_t seed_lo, uint32_t seed_hi, uint32_t hop, int m, const uint32_t* __restrict__ edge_weight, int& filled) {
+// Selection for the R roots of a group whose cutoffs are known. Leaves, in lane `sub` of the
+// group, the record of output slot `sub` of every root (padding from slot `filled` on). Written in
+// stages over all R roots, so that the loads of one stage (the last k records; the candidate window
+// and then its weights; the uniformly drawn records) are in flight for all of them together, with
+// the draws' arithmetic in between. Every lane of the wave must call it.
+template <int POLICY, int G, int R>
+__device__ __forceinline__ void select_slots(
+    const TaserRec* __restrict__ rec, int64_t q0, const uint32_t (&lo)[R], const uint32_t (&cnt)[R], int group, int sub, int k,
+    uint32_t seed_lo, uint32_t seed_hi, uint32_t hop, int m, const uint32_t* __restrict__ edge_weight,
+    TaserRec (&out)[R], int (&filled)[R]) {
     const TaserRec pad = {0, -1, -1};
-    TaserRec out = pad;
 
     // All lanes of the wave walk through the same code; what a group does not need is masked.
     if (POLICY == TASER_RECENT) {
-        filled = (int)(cnt < k ? cnt : k);
-        if (sub < filled) out = rec[lo + cnt - 1 - sub];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            filled[r] = (int)(cnt[r] < (uint32_t)k ? cnt[r] : (uint32_t)k);
+            out[r] = pad;
+            if (sub < filled[r]) out[r] = rec[lo[r] + cnt[r] - 1u - (uint32_t)sub];
+        }
     } else if (POLICY == TASER_UNIFORM) {
         // cnt <= k: everything, most recent first. Otherwise a partial Fisher-Yates
         // over the virtual array a[x] = x, x in [0, cnt): lane j of the group owns
         // step j; it remembers the position it overwrote (pos) and the value it put
         // there (val); a lookup of a[x] at step j is the val of the latest earlier
         // step that wrote x, else x itself.
-        const bool shuffle = cnt > k;
-        filled = (int)(shuffle ? k : cnt);
-        uint32_t pos = 0, val = 0, idx = 0;
-        if (shuffle && sub < k) {
-            const uint64_t u = draw64(seed_lo, seed_hi, hop, (uint64_t)q, (uint32_t)sub);
-            pos = (uint32_t)sub + (uint32_t)__umul64hi(u, (uint64_t)(cnt - sub));
-        }
-        if (__ballot(shuffle)) {
-            for (int j = 0; j < k; ++j) {
-                const uint32_t r = group_get<G>(pos, j);
-                const bool earlier = sub < j;
-                const uint64_t hit_r = group_bits<G>(__ballot(earlier && pos == r), group);
-                const uint64_t hit_j = group_bits<G>(__ballot(earlier && pos == (uint32_t)j), group);
-                // the shuffles are executed by every lane; lanes without a hit read lane 0 and drop it
-                const uint32_t v_r = group_get<G>(val, hit_r ? 63 - __clzll((long long)hit_r) : 0);
-                const uint32_t v_j = group_get<G>(val, hit_j ? 63 - __clzll((long long)hit_j) : 0);
-                if (sub == j) {
-                    idx = hit_r ? v_r : r;
-                    val = hit_j ? v_j : (uint32_t)j;
+        uint32_t at[R];   // list position of this lane's slot
+        bool some[R];     // false: padding
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const bool shuffle = cnt[r] > (uint32_t)k;
+            filled[r] = shuffle ? k : (int)cnt[r];
+            uint32_t pos = 0, val = 0, idx = 0;
+            if (shuffle && sub < k) {
+                const uint64_t u = draw64(seed_lo, seed_hi, hop, (uint64_t)(q0 + r), (uint32_t)sub);
+                pos = (uint32_t)sub + mulhi_64x32(u, cnt[r] - (uint32_t)sub);
+            }
+            if (__ballot(shuffle)) {
+                for (int j = 0; j < k; ++j) {
+                    const uint32_t x = group_get<G>(pos, j);
+                    const bool earlier = sub < j;
+                    const uint64_t hit_x = group_bits<G>(__ballot(earlier && pos == x), group);
+                    const uint64_t hit_j = group_bits<G>(__ballot(earlier && pos == (uint32_t)j), group);
+                    // the shuffles are executed by every lane; lanes without a hit read lane 0 and drop it
+                    const uint32_t v_x = group_get<G>(val, hit_x ? 63 - __clzll((long long)hit_x) : 0);
+                    const uint32_t v_j = group_get<G>(val, hit_j ? 63 - __clzll((long long)hit_j) : 0);
+                    if (sub == j) {
+                        idx = hit_x ? v_x : x;
+                        val = hit_j ? v_j : (uint32_t)j;
+                    }
+                }
+            }
+            at[r] = 0;
+            some[r] = false;
+            if (sub < k) {
+                if (shuffle) {
+                    at[r] = idx;
+                    some[r] = true;
+                } else if (sub < filled[r]) {
+                    at[r] = cnt[r] - 1u - (uint32_t)sub;
+                    some[r] = true;
                 }
             }
         }
-        if (sub < k) {
-            if (shuffle) out = rec[lo + idx];
-            else if (sub < filled) out = rec[lo + cnt - 1 - sub];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            out[r] = pad;
+            if (some[r]) out[r] = rec[lo[r] + at[r]];
         }
     } else {
         // Candidate window: lane i of the group holds candidate i (the i-th most recent);
         // lane j notes which candidate draw j picked and fetches it from that lane at the end.
-        const int c = (int)(cnt < m ? cnt : m);
-        TaserRec mine = pad;
-        uint64_t w = 0;
-        if (sub < c) {
-            mine = rec[lo + cnt - 1 - sub];
-            w = edge_weight[mine.eid];
+        TaserRec mine[R];
+        uint64_t w[R];
+        int c[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            c[r] = (int)(cnt[r] < (uint32_t)m ? cnt[r] : (uint32_t)m);
+            mine[r] = pad;
+            if (sub < c[r]) mine[r] = rec[lo[r] + cnt[r] - 1u - (uint32_t)sub];
         }
-        const bool draw = c > k;
-        filled = draw ? k : c;
-        int my_pick = (!draw && sub < c) ? sub : -1;
-        if (__ballot(draw)) {
-            uint64_t u = 0;
-            if (draw && sub < k) u = draw64(seed_lo, seed_hi, hop, (uint64_t)q, (uint32_t)sub);
-            // running sums of the weights once; every draw then only takes its pick out of them
-            uint64_t run = group_inclusive_scan64<G>(w, sub);
-            uint64_t total = group_get64<G>(run, G - 1);
-            for (int j = 0; j < k; ++j) {
-                const int pick = group_weighted_pick<G>(run, total, w, group_get64<G>(u, j), draw, group, sub);
-                if (draw && sub == j) my_pick = pick;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            w[r] = 0;
+            if (sub < c[r]) w[r] = edge_weight[mine[r].eid];
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const bool draw = c[r] > k;
+            filled[r] = draw ? k : c[r];
+            int my_pick = (!draw && sub < c[r]) ? sub : -1;
+            if (__ballot(draw)) {
+                uint64_t u = 0;
+                if (draw && sub < k) u = draw64(seed_lo, seed_hi, hop, (uint64_t)(q0 + r), (uint32_t)sub);
+                // running sums of the weights once; every draw then only takes its pick out of them
+                uint64_t run = group_inclusive_scan64<G>(w[r], sub);
+                uint64_t total = group_get64<G>(run, G - 1);
+                for (int j = 0; j < k; ++j) {
+                    const int pick = group_weighted_pick<G>(run, total, w[r], group_get64<G>(u, j), draw, group, sub);
+                    if (draw && sub == j) my_pick = pick;
+                }
             }
+            const int from = my_pick < 0 ? 0 : my_pick;   // the shuffles are executed by every lane
+            const int32_t p_nbr = (int32_t)group_get<G>((uint32_t)mine[r].nbr, from);
+            const int32_t p_eid = (int32_t)group_get<G>((uint32_t)mine[r].eid, from);
+            const int64_t p_ts = (int64_t)group_get64<G>((uint64_t)mine[r].ts, from);
+            out[r] = pad;
+            if (my_pick >= 0 && sub < k) out[r] = TaserRec{p_ts, p_nbr, p_eid};
         }
-        const int from = my_pick < 0 ? 0 : my_pick;   // the shuffles are executed by every lane
-        const int32_t p_nbr = (int32_t)group_get<G>((uint32_t)mine.nbr, from);
-        const int32_t p_eid = (int32_t)group_get<G>((uint32_t)mine.eid, from);
-        const int64_t p_ts = (int64_t)group_get64<G>((uint64_t)mine.ts, from);
-        if (my_pick >= 0 && sub < k) out = TaserRec{p_ts, p_nbr, p_eid};
     }
-    return out;
 }
 
 // G lanes per root: G >= k, and G >= m for the weighted policy. A group serves
 // kRootsPerGroup consecutive roots: their searches run side by side, their selections
-// one after the other (measured: two roots per group pay for the most-recent finder on
-// large hops, 39 -> 32 us for 120 000 roots; they cost the heavier selections 10 %).
+// stage by stage (measured: two roots per group pay for the most-recent finder on large
+// hops, 39 -> 32 us for 120 000 roots; the uniform and weighted finders, whose time is
+// mostly the arithmetic of their draws, gain nothing from them).
 template <int POLICY, int G, int kRootsPerGroup>
 __global__ __launch_bounds__(kThreads) void sample_hop_kernel(
     const int64_t* __restrict__ indptr, const TaserRec* __restrict__ rec, const TaserTimeIndex index,
@@ -212,30 +257,32 @@ __global__ __launch_bounds__(kThreads) void sample_hop_kernel(
     const int group = lane / G, sub = lane % G;
     const int64_t q0 = (((int64_t)blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6)) * kGroups + group) * kRootsPerGroup;
 
-    int64_t lo[kRootsPerGroup], hi[kRootsPerGroup], t[kRootsPerGroup], cnt[kRootsPerGroup];
+    uint32_t lo[kRootsPerGroup], hi[kRootsPerGroup], cnt[kRootsPerGroup];   // positions fit 32 bits: fewer than 2^31 entries
+    int64_t t[kRootsPerGroup];
     int32_t v[kRootsPerGroup];
 #pragma unroll
     for (int r = 0; r < kRootsPerGroup; ++r) {
-        lo[r] = hi[r] = t[r] = 0;
+        lo[r] = hi[r] = 0;
+        t[r] = 0;
         v[r] = q0 + r < num_roots ? roots[q0 + r] : -1;
     }
 #pragma unroll
     for (int r = 0; r < kRootsPerGroup; ++r) {
         if (v[r] >= 0 && v[r] < num_nodes) {   // anything else is a root without neighbors
             t[r] = times[q0 + r];
-            lo[r] = indptr[v[r]];
-            hi[r] = indptr[v[r] + 1];
+            lo[r] = (uint32_t)indptr[v[r]];
+            hi[r] = (uint32_t)indptr[v[r] + 1];
         }
     }
     group_cutoff<G, kRootsPerGroup>(rec, index, lo, hi, t, group, sub, cnt);   // 0 for dead roots (lo == hi)
+    TaserRec slot[kRootsPerGroup];
+    int filled[kRootsPerGroup];
+    select_slots<POLICY, G, kRootsPerGroup>(rec, q0, lo, cnt, group, sub, k, seed_lo, seed_hi, hop, m, edge_weight, slot, filled);
 #pragma unroll
     for (int r = 0; r < kRootsPerGroup; ++r) {
-        int filled;
-        const TaserRec slot = select_slot<POLICY, G>(rec, q0 + r, lo[r], cnt[r], group, sub, k, seed_lo, seed_hi, hop, m,
-                                                     edge_weight, filled);
         if (q0 + r < num_roots) {
-            if (sub < k) store_slot(o_nbr, o_eid, o_ts, (q0 + r) * k + sub, slot);
-            if (sub == 0) o_count[q0 + r] = filled;
+            if (sub < k) store_slot(o_nbr, o_eid, o_ts, (q0 + r) * k + sub, slot[r]);
+            if (sub == 0) o_count[q0 + r] = filled[r];
         }
     }
 }

@@ -31,6 +31,12 @@ __device__ __forceinline__ uint64_t draw64(uint32_t seed_lo, uint32_t seed_hi, u
     return ((uint64_t)c[1] << 32) | c[0];
 }
 
+// floor(u * n / 2^64) for a 32-bit n: the high word of the 96-bit product.
+__device__ __forceinline__ uint32_t mulhi_64x32(uint64_t u, uint32_t n) {
+    const uint64_t low = (uint64_t)(uint32_t)u * n;                    // contributes its high word as a carry
+    return (uint32_t)(((u >> 32) * n + (low >> 32)) >> 32);
+}
+
 // ---- group helpers ---------------------------------------------------------
 // A wavefront is split into 64/G groups of G consecutive lanes (G = 16, 32 or
 // 64), one root per group. `sub` is a lane's index inside its group.
