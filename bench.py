@@ -438,8 +438,9 @@ def main():
         ref = oracle.sample_temporal(g_ref, roots[:nr], times[:nr], k, hops, policy, 42, w.m, w.edge_weight, threads)
         t_sample = time.perf_counter() - t0
         t0 = time.perf_counter()
+        node_ref = None
         if w.node_feat is not None:
-            oracle.gather(w.node_feat, np.concatenate([roots[:nr]] + [o["nbr"].ravel() for o in ref]), threads=threads)
+            node_ref = oracle.gather(w.node_feat, np.concatenate([roots[:nr]] + [o["nbr"].ravel() for o in ref]), threads=threads)
         if w.edge_feat is not None:
             oracle.gather(w.edge_feat, np.concatenate([o["eid"].ravel() for o in ref]), threads=threads)
         t_gather = time.perf_counter() - t0
@@ -452,6 +453,14 @@ def main():
             for f in ("nbr", "eid", "ts"):
                 assert np.array_equal(got[h][f][:nr * k ** (h + 1)].cpu().numpy(), ref[h][f].ravel()), f"GPU/oracle mismatch: hop {h} {f}"
             assert np.array_equal(got[h]["count"][:nr * k ** h].cpu().numpy(), ref[h]["count"].ravel()), f"GPU/oracle mismatch: hop {h} count"
+        if node_ref is not None:
+            # the node rows the device served for those roots and their sampled neighbors (run(0, 1) left them in node_out[0])
+            at, parts, r_h = 0, [node_out[0][:nr]], R
+            for h in range(hops):
+                at += r_h
+                r_h *= k
+                parts.append(node_out[0][at:at + nr * k ** (h + 1)])
+            assert torch.cat(parts).cpu().numpy().tobytes() == node_ref.tobytes(), "GPU/oracle mismatch: node rows"
         sample = (f"first {nr} roots of batch 0, {hops} hops: sampler {t_sample:.2f}s + "
                   f"{'node' if w.edge_feat is None else 'edge'}-feature gather {t_gather:.2f}s; "
                   f"oracle T-CSR build ({t_build:.1f}s) not included")

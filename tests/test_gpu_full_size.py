@@ -126,6 +126,13 @@ def test_c5_full_size_whole_batch_parity_and_properties():
     cache = T.cache_init(node_host, cap, hot, staging_rows=w.num_nodes - cap)
     T.cache_tune(cache, stage_blocks=16, refresh_before_gather=True)
     ids = torch.cat([dev(roots), got[0]["nbr"].reshape(-1), got[1]["nbr"].reshape(-1)])
+    # as in bench.py: one counted pass and an epoch end first, which also marks the most requested rows
+    # (the gather spreads those over the L2 partitions by position)
+    T.cache_count_accesses(cache)
+    T.cache_prefetch(cache, ids)
+    replaced, overlap = T.cache_epoch_end(cache, min_overlap=0)
+    T.cache_count_accesses(cache, False)
+    assert not replaced and 0 < overlap <= cap
     hm = torch.zeros(2, dtype=torch.int64, device="cuda")
     main, side = torch.cuda.current_stream(), torch.cuda.Stream()
     ready, staged = torch.cuda.Event(), torch.cuda.Event()
