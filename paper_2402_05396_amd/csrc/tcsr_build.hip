@@ -150,23 +150,38 @@ __global__ __launch_bounds__(kThreads) void fold_info_kernel(const unsigned long
     }
 }
 
-// hist[bin * num_blocks + block] = items of this block's tile whose digit is bin.
+// Tile of a workgroup of the scatter: workgroups go to the chip's eight L2 partitions round-robin;
+// each partition takes a contiguous eighth of the tiles, so that the short runs of one digit that
+// its workgroups write one after the other into neighboring addresses (16 records per tile on
+// average for 256 digits) meet in its L2 and leave as whole lines. With tile = workgroup index
+// those pieces came from eight different L2s as partial lines (5.8 -> 3.6 ms for the 256-digit
+// pass over 382 M entries). The grid is rounded up to a multiple of kPartitions; tiles >=
+// num_blocks do not exist.
+constexpr uint32_t kPartitions = 8;
+__device__ __forceinline__ uint32_t tile_of_block(uint32_t block, uint32_t num_blocks) {
+    const uint32_t per_part = (num_blocks + kPartitions - 1) / kPartitions;
+    return (block % kPartitions) * per_part + block / kPartitions;
+}
+inline unsigned pass_grid(unsigned num_blocks) { return (num_blocks + kPartitions - 1) / kPartitions * kPartitions; }
+
+// hist[bin * num_blocks + tile] = items of the tile whose digit is bin.
 __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const TaserRec* __restrict__ rec,
                                                               const int32_t* __restrict__ key, int64_t n,
                                                               DigitSpec d, uint32_t* __restrict__ hist,
                                                               uint32_t num_blocks) {
     __shared__ uint32_t bins[kBins];
+    const uint32_t tile = blockIdx.x;   // (the partition-wise order of the scatter below does not pay here)
     bins[threadIdx.x] = 0;
     __syncthreads();
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const int64_t tile0 = (int64_t)blockIdx.x * kTile;
+    const int64_t tile0 = (int64_t)tile * kTile;
 #pragma unroll 4
     for (int r = 0; r < kItems; ++r) {
         const int64_t i = item_index(tile0, wave, r, lane);
         if (i < n) atomicAdd(&bins[digit_at(rec, key, i, d)], 1u);
     }
     __syncthreads();
-    hist[(size_t)threadIdx.x * num_blocks + blockIdx.x] = bins[threadIdx.x];
+    hist[(size_t)threadIdx.x * num_blocks + tile] = bins[threadIdx.x];
 }
 
 // Stable scatter of one tile. offs = the scanned histogram: offs[bin*num_blocks
@@ -192,9 +207,11 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
     __shared__ TaserRec tile_rec[kPart];
     __shared__ int32_t tile_key[kPart];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const int64_t tile0 = (int64_t)blockIdx.x * kTile;
+    const uint32_t tile = tile_of_block(blockIdx.x, num_blocks);
+    if (tile >= num_blocks) return;
+    const int64_t tile0 = (int64_t)tile * kTile;
     for (int w = 0; w < kWaves; ++w) wave_count[w][threadIdx.x] = 0;
-    block_base[threadIdx.x] = offs[(size_t)threadIdx.x * num_blocks + blockIdx.x];
+    block_base[threadIdx.x] = offs[(size_t)threadIdx.x * num_blocks + tile];
     __syncthreads();
 
     uint32_t digit[kItems], rank[kItems];
@@ -434,7 +451,7 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
             }
             {
                 TaserProfileSpan span(stream, "tcsr_radix_scatter");
-                hipLaunchKernelGGL(radix_scatter_kernel, dim3(num_blocks), dim3(kThreads), 0, stream,
+                hipLaunchKernelGGL(radix_scatter_kernel, dim3(pass_grid(num_blocks)), dim3(kThreads), 0, stream,
                                    rec_a.as<TaserRec>(), key_a.as<int32_t>(), n, d, hist.as<uint32_t>(), num_blocks,
                                    rec_b.as<TaserRec>(), key_b.as<int32_t>());
             }
