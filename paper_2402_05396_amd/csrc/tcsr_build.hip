@@ -175,10 +175,28 @@ __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const TaserRec* __
     __syncthreads();
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const int64_t tile0 = (int64_t)tile * kTile;
+    if (!d.from_ts && tile0 + kTile <= n) {
+        // a whole tile of node keys: which thread counts which item does not matter, so every thread
+        // takes four runs of four keys with 16-byte loads (tile0 is a multiple of the tile size and
+        // `key` the start of an allocation: aligned), all four loads in flight together
+        typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+        const i32x4* quads = reinterpret_cast<const i32x4*>(key + tile0);
+        i32x4 v[kItems / 4];
+#pragma unroll
+        for (int r = 0; r < kItems / 4; ++r) v[r] = quads[r * kThreads + threadIdx.x];
+#pragma unroll
+        for (int r = 0; r < kItems / 4; ++r) {
+            atomicAdd(&bins[((uint32_t)v[r].x >> d.shift) & d.mask], 1u);
+            atomicAdd(&bins[((uint32_t)v[r].y >> d.shift) & d.mask], 1u);
+            atomicAdd(&bins[((uint32_t)v[r].z >> d.shift) & d.mask], 1u);
+            atomicAdd(&bins[((uint32_t)v[r].w >> d.shift) & d.mask], 1u);
+        }
+    } else {
 #pragma unroll 4
-    for (int r = 0; r < kItems; ++r) {
-        const int64_t i = item_index(tile0, wave, r, lane);
-        if (i < n) atomicAdd(&bins[digit_at(rec, key, i, d)], 1u);
+        for (int r = 0; r < kItems; ++r) {
+            const int64_t i = item_index(tile0, wave, r, lane);
+            if (i < n) atomicAdd(&bins[digit_at(rec, key, i, d)], 1u);
+        }
     }
     __syncthreads();
     hist[(size_t)threadIdx.x * num_blocks + tile] = bins[threadIdx.x];
@@ -303,14 +321,28 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
     }
 }
 
-// indptr[v] = first position whose node id is >= v, from the sorted node column.
+// indptr[v] = first position whose node id is >= v, from the sorted node column: position p starts
+// the lists of the nodes in (key[p - 1], key[p]]. A thread looks at four consecutive positions (one
+// 16-byte load; `key` is the start of an allocation) plus the key before them.
 __global__ __launch_bounds__(kThreads) void indptr_kernel(const int32_t* __restrict__ key, int64_t n,
                                                           int32_t num_nodes, int64_t* __restrict__ indptr) {
-    const int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (p > n) return;
-    const int32_t prev = p > 0 ? key[p - 1] : -1;
-    const int32_t cur = p < n ? key[p] : num_nodes;
-    for (int32_t v = prev + 1; v <= cur; ++v) indptr[v] = p;
+    typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+    const int64_t p0 = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4;
+    if (p0 > n) return;
+    int32_t k[5];   // k[0] = the key before p0, k[1 + j] = key at p0 + j (num_nodes from position n on)
+    k[0] = p0 > 0 ? key[p0 - 1] : -1;
+    if (p0 + 4 <= n) {
+        const i32x4 v = *reinterpret_cast<const i32x4*>(key + p0);
+        k[1] = v.x; k[2] = v.y; k[3] = v.z; k[4] = v.w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) k[1 + j] = p0 + j < n ? key[p0 + j] : num_nodes;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (p0 + j > n) break;
+        for (int32_t v = k[j] + 1; v <= k[1 + j]; ++v) indptr[v] = p0 + j;
+    }
 }
 
 __global__ __launch_bounds__(kThreads) void unpack_kernel(const TaserRec* __restrict__ rec, int64_t n,
@@ -461,7 +493,7 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
     }
     {
         TaserProfileSpan span(stream, "tcsr_indptr");
-        hipLaunchKernelGGL(indptr_kernel, dim3(blocks_for(n + 1, kThreads)), dim3(kThreads), 0, stream,
+        hipLaunchKernelGGL(indptr_kernel, dim3(blocks_for(n + 1, kThreads * 4)), dim3(kThreads), 0, stream,
                            key_a.as<int32_t>(), n, num_nodes, indptr.as<int64_t>());
     }
     // ---- search index over the sorted timestamps
