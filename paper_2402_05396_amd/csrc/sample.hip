@@ -150,10 +150,8 @@ __device__ __forceinline__ void select_slots(
         }
     } else if (POLICY == TASER_UNIFORM) {
         // cnt <= k: everything, most recent first. Otherwise a partial Fisher-Yates
-        // over the virtual array a[x] = x, x in [0, cnt): lane j of the group owns
-        // step j; it remembers the position it overwrote (pos) and the value it put
-        // there (val); a lookup of a[x] at step j is the val of the latest earlier
-        // step that wrote x, else x itself.
+        // over the virtual array a[x] = x, x in [0, cnt): step j draws pos_j in
+        // [j, cnt), takes a[pos_j] and puts a[j] there; lane j of the group owns step j.
         uint32_t at[R];   // list position of this lane's slot
         bool some[R];     // false: padding
 #pragma unroll
@@ -166,17 +164,48 @@ __device__ __forceinline__ void select_slots(
                 pos = (uint32_t)sub + mulhi_64x32(u, cnt[r] - (uint32_t)sub);
             }
             if (__ballot(shuffle)) {
-                for (int j = 0; j < k; ++j) {
-                    const uint32_t x = group_get<G>(pos, j);
-                    const bool earlier = sub < j;
-                    const uint64_t hit_x = group_bits<G>(__ballot(earlier && pos == x), group);
-                    const uint64_t hit_j = group_bits<G>(__ballot(earlier && pos == (uint32_t)j), group);
-                    // the shuffles are executed by every lane; lanes without a hit read lane 0 and drop it
-                    const uint32_t v_x = group_get<G>(val, hit_x ? 63 - __clzll((long long)hit_x) : 0);
-                    const uint32_t v_j = group_get<G>(val, hit_j ? 63 - __clzll((long long)hit_j) : 0);
-                    if (sub == j) {
-                        idx = hit_x ? v_x : x;
-                        val = hit_j ? v_j : (uint32_t)j;
+                if (G <= 32) {
+                    // Every lane resolves its own step from the positions all steps drew (no values
+                    // need to travel): a[x] at step j is x unless an earlier step wrote x; the latest
+                    // such step i put there what position i held at step i, which is the same question
+                    // for (i, i). Chains are short: one pass when no two steps of a root collide.
+                    uint32_t drawn[G];
+#pragma unroll
+                    for (int i = 0; i < G; ++i) drawn[i] = group_get<G>(pos, i);
+                    uint32_t x = pos;
+                    int before = sub;                       // only steps below this one count
+                    bool open = shuffle && sub < k;
+                    while (__ballot(open)) {
+                        int found = -1;
+#pragma unroll
+                        for (int i = 0; i < G; ++i)
+                            if (i < before && drawn[i] == x) found = i;   // ascending: the latest match stays
+                        if (open) {
+                            if (found < 0) {
+                                open = false;
+                            } else {
+                                x = (uint32_t)found;
+                                before = found;
+                            }
+                        }
+                    }
+                    idx = x;
+                } else {
+                    // lane j of the group owns step j; it remembers the position it overwrote (pos) and
+                    // the value it put there (val); a lookup of a[x] at step j is the val of the latest
+                    // earlier step that wrote x, else x itself
+                    for (int j = 0; j < k; ++j) {
+                        const uint32_t x = group_get<G>(pos, j);
+                        const bool earlier = sub < j;
+                        const uint64_t hit_x = group_bits<G>(__ballot(earlier && pos == x), group);
+                        const uint64_t hit_j = group_bits<G>(__ballot(earlier && pos == (uint32_t)j), group);
+                        // the shuffles are executed by every lane; lanes without a hit read lane 0 and drop it
+                        const uint32_t v_x = group_get<G>(val, hit_x ? 63 - __clzll((long long)hit_x) : 0);
+                        const uint32_t v_j = group_get<G>(val, hit_j ? 63 - __clzll((long long)hit_j) : 0);
+                        if (sub == j) {
+                            idx = hit_x ? v_x : x;
+                            val = hit_j ? v_j : (uint32_t)j;
+                        }
                     }
                 }
             }
