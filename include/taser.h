@@ -237,7 +237,7 @@ int taser_gather_features(const void* table, int64_t rows, int32_t row_bytes,
  *                   (hipHostMalloc / a pinned torch tensor); it must outlive
  *                   the handle. TASER_E_ARG if it is not such memory.
  *   rows, row_bytes, pitch_bytes   as for taser_gather_features; row_bytes % 4 == 0
- *   capacity_rows   in [0, rows]
+ *   capacity_rows   in [0, rows], below 2^30
  *   resident_ids    host int32[capacity_rows], distinct, in [0, rows); or NULL:
  *                   the first capacity_rows elements of a partial Fisher-Yates
  *                   shuffle of 0..rows-1 with draw j keyed (seed, hop tag
@@ -336,7 +336,7 @@ int taser_cache_tune(taser_cache* c, int32_t stage_blocks, int32_t refresh_befor
  * The counters (uint32 per row, device memory, zeroed when first enabled) and
  * the scratch of taser_cache_epoch_end (two more uint32 per row, one int32 per
  * cache slot) are allocated when counting is first enabled, so an epoch end
- * allocates nothing; enable == 0 pauses counting and keeps them.
+ * allocates no device memory; enable == 0 pauses counting and keeps them.
  *
  * taser_cache_access_counts copies the counters into `counts`
  * (device uint32[rows], caller-allocated), ordered on `hip_stream`.
