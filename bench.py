@@ -57,6 +57,11 @@ def main():
                          "(both streams, forked and joined by events inside the capture) and the replay is what "
                          "`value` reports; eager: launches one by one only")
     ap.add_argument("--graph", action="store_true", help="same as --launch graph (the default)")
+    ap.add_argument("--edge-rows", default="auto", choices=["auto", "finder", "gather"],
+                    help="finder: one call finds the neighbors and slices their edge rows (taser_sample_temporal_rows: short rows "
+                         "are written by the hop kernels, long ones by one gather launch after the last hop); gather: "
+                         "taser_sample_temporal, then taser_gather_features; auto: finder unless a node cache is in the step "
+                         "(its schedule puts the late node gather between the sampling and the edge gather)")
     ap.add_argument("--no-refresh", action="store_true", help="do not re-write the gather's working set before the node gather")
     ap.add_argument("--flat-gather", action="store_true", help="node gather in plain output order instead of by L2 partition")
     ap.add_argument("--cache-ratio", type=float, default=None,
@@ -187,8 +192,25 @@ def main():
     ev_sampled = [torch.cuda.Event() for _ in range(n_buf)]
     ev_staged = [torch.cuda.Event() for _ in range(n_buf)]
 
-    def sample(b):
-        T.sample_temporal(g, b["roots"], b["times"], k, hops, policy, 42, w.m, weight, out=b["out"], stream=main)
+    rows_call = args.edge_rows == "finder" or (args.edge_rows == "auto" and cache is None)   # one call for neighbors and edge rows
+    edge_rows = []                                   # per buffer set: one view of edge_out per hop
+    for s in range(n_buf):
+        views, at = [], 0
+        for h in range(hops):
+            views.append(edge_out[s][at:at + n_slots[h]])
+            at += n_slots[h]
+        edge_rows.append(views)
+
+    def sample(b, s):
+        if rows_call:
+            T.sample_temporal_rows(g, b["roots"], b["times"], k, hops, policy, 42, edge_table, m=w.m, edge_weight=weight,
+                                   out=b["out"], rows_out=edge_rows[s], stream=main)
+        else:
+            T.sample_temporal(g, b["roots"], b["times"], k, hops, policy, 42, w.m, weight, out=b["out"], stream=main)
+
+    def edge_gather(b, s):
+        if not rows_call:
+            T.gather_features(edge_table, b["eids"], out=edge_out[s], stream=main)
 
     def run(first, count):
         """`count` passes of the whole path over consecutive batches.
@@ -202,9 +224,9 @@ def main():
         pending = None
         for i in range(count):
             b, s = batches[(first + i) % len(batches)], i % n_buf
-            sample(b)
+            sample(b, s)
             if cache is None or args.schedule == "serial":
-                T.gather_features(edge_table, b["eids"], out=edge_out[s], stream=main)
+                edge_gather(b, s)
                 if cache is not None:
                     T.cache_lookup(caches[s], b["ids"], out=node_out[s], hit_miss=hit_miss, stream=main)
                 continue
@@ -218,9 +240,9 @@ def main():
                     main.wait_event(ev_staged[ps])
                     T.cache_gather(caches[ps], pb["ids"], out=node_out[ps], stream=main)
                 pending = (b, s)
-                T.gather_features(edge_table, b["eids"], out=edge_out[s], stream=main)
+                edge_gather(b, s)
                 continue
-            T.gather_features(edge_table, b["eids"], out=edge_out[s], stream=main)
+            edge_gather(b, s)
             if args.schedule == "pipeline":
                 if pending is not None:
                     pb, ps = pending
@@ -242,7 +264,10 @@ def main():
     run(0, max(args.warmup, 1))
     torch.cuda.synchronize()
     warm = T.profile_end()
-    dominant = max((n for n in warm if n in ("cache_gather_rows", "gather_rows")), key=lambda n: warm[n][1])
+    # (with the edge rows written by the hop kernels, those kernels stand for the edge gather)
+    finder_names = [n for n in warm if n.startswith("sample_rows_")]
+    fused = bool(finder_names)                       # short rows: the hop kernels wrote them; else the call launched the gather
+    dominant = max((n for n in warm if n in ("cache_gather_rows", "gather_rows") or n in finder_names), key=lambda n: warm[n][1])
     hit_miss.zero_()
     torch.cuda.synchronize()
 
@@ -323,6 +348,8 @@ def main():
     alg_of = {"cache_gather_rows": node_bytes, "gather_rows": edge_bytes}
     hbm_of = {"cache_gather_rows": node_hbm, "gather_rows": edge_hbm}
     out_bytes = {"cache_gather_rows": n_ids * node_rb, "gather_rows": sum(n_slots) * edge_rb}
+    for n in finder_names:          # one launch per hop under one name: bytes per average launch
+        alg_of[n], hbm_of[n], out_bytes[n] = edge_bytes / hops, edge_hbm / hops, sum(n_slots) * edge_rb / hops
     roofline = None
     if dominant in hbm_of:
         dom_ms = dominant_time[1] / dominant_time[0]            # measured inside the timed region
@@ -333,8 +360,10 @@ def main():
                     "avg_launch_ms": round(dom_ms, 4), "launches_timed": dominant_time[0],
                     "hbm_bytes": int(hbm_of[dominant]),
                     "bytes_note": "achieved = (dense output + 4 B id per row + every distinct source row once) / "
-                                  "average launch time inside the eager timed region (events cannot be read back from a graph)",
-                    "algorithmic_bytes": alg_of[dominant],
+                                  "average launch time inside the eager timed region (events cannot be read back from a graph)"
+                                  + ("; this kernel finds the neighbors and writes their edge rows, one launch per hop: "
+                                     "the bytes are the edge rows' alone, averaged over the hops" if dominant in finder_names else ""),
+                    "algorithmic_bytes": int(alg_of[dominant]),
                     "algorithmic_GBps": round(alg_of[dominant] / (dom_ms * 1e-3) / 1e9, 1),
                     "algorithmic_note": "rows x (row read + row written + id): repeated source rows are served by "
                                         "L2, so this figure can exceed the HBM peak and is not a roofline fraction",
@@ -365,8 +394,15 @@ def main():
                                       "bound by dependent-read latency, not bytes: per root 16 B of list bounds + 4 B count + "
                                       "about 7 index/record probes of 8 B; per kept neighbor 16 B read + 16 B written"),
                               neighbors_per_s=round(neighbors / args.steps / (sample_ms * 1e-3), 1)),
-        "a7_edge_gather": hbm_row(edge_hbm, edge_bytes, per_kernel["gather_rows"]["avg_ms"]),
     }
+    if fused:
+        del rows_report["a2_a6_sampler"]
+        rows_report["a2_a7_sampler_writing_edge_rows"] = dict(
+            hbm_row(sampler_bytes + edge_hbm, sampler_bytes + edge_bytes, sample_ms,
+                    "one launch per hop finds the neighbors and copies their edge rows (searching wavefronts run beside copying ones)"),
+            neighbors_per_s=round(neighbors / args.steps / (sample_ms * 1e-3), 1))
+    else:
+        rows_report["a7_edge_gather"] = hbm_row(edge_hbm, edge_bytes, per_kernel["gather_rows"]["avg_ms"])
     step_hbm_bytes = sampler_bytes + edge_hbm
     if cache is not None:
         lookup_ms = sum(per_kernel[n]["avg_ms"] for n in ("cache_classify", "cache_refresh_working_set", "cache_gather_rows")
@@ -507,6 +543,8 @@ def main():
                    "node_row_bytes": node_rb, "distinct_batches": len(batches),
                    "cache_rows": (0 if cache is None else cache.capacity) if args.cache_ratio is None
                    else f"{cache.capacity} (override)", "schedule": args.schedule,
+                   "edge_rows": ("taser_sample_temporal_rows: " if rows_call else "taser_sample_temporal, taser_gather_features: ")
+                   + ("written by the hop kernels" if fused else "one gather launch after the last hop"),
                    "launch": launch},
         "sampler_neighbors_per_s": round(neighbors / args.steps / (sum(ms for n, (c, ms) in kernels.items()
                                                                        if n.startswith("sample_")) / args.steps * 1e-3), 1),

@@ -17,7 +17,7 @@
  *   - Return value: TASER_OK (0) or a negative taser_status. Arguments are
  *     validated on the host before anything is launched; on error nothing has
  *     been enqueued and taser_last_error() describes the problem.
- *   - Graph capture: taser_sample_temporal, taser_gather_features,
+ *   - Graph capture: taser_sample_temporal(_rows), taser_gather_features,
  *     taser_candidate_encodings, taser_select_weighted, taser_selector_draw,
  *     taser_selector_update and taser_cache_lookup / _lookup_static /
  *     _prefetch / _gather only launch kernels (no memset or copy nodes, no
@@ -167,6 +167,37 @@ int taser_sample_temporal(const taser_tcsr* g, const int32_t* roots, const int64
                           int64_t num_roots, int32_t k, int32_t hops, int32_t policy,
                           uint64_t seed, int32_t m, const uint32_t* edge_weight,
                           const taser_hop_out* out, void* hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * Neighbor finding with the sampled edges' feature rows (Alg. 1: every layer's
+ * neighbors are found, then their features sliced, Sec. 3.4 / Alg. 3 line 8;
+ * here one launch per hop does both). The result is exactly that of
+ *   taser_sample_temporal(g, roots, ..., out, stream) followed, for every hop h, by
+ *   taser_gather_features(table, table_rows, row_bytes, pitch_bytes,
+ *                         out[h].eid, R_h * k, rows_out[h], stream):
+ * row q of rows_out[h] holds the table row of slot q's edge id, zeros for a
+ * padding slot or an id outside [0, table_rows). While the rows of one
+ * wavefront's roots are at most 8 KiB ((64 / G) * k * row_bytes, G = 16, 32 or
+ * 64 being the first of them that holds k, and m for TASER_WEIGHTED), the
+ * wavefront that has found the neighbors copies their rows itself: no launch of
+ * its own for the rows, and the edge ids are not read back from memory. That
+ * needs row_bytes a multiple of 4 and >= 16, table and pitch_bytes multiples of
+ * 4, rows_out[h] 16-byte aligned and those bytes per wavefront a multiple of
+ * 16. A hop for which any of it fails, every hop with longer rows (for which a
+ * gather launch is the faster way) and every hop of TASER_INVERSE_TIMESPAN get
+ * their rows from the gather kernel after the last hop, in one launch where the
+ * hops' edge id arrays and row buffers follow one another in memory. The bytes
+ * are the same either way.
+ *   sampling arguments, `out`: as for taser_sample_temporal
+ *   table, table_rows, row_bytes, pitch_bytes: as for taser_gather_features
+ *   rows_out  host array of `hops` device pointers; rows_out[h] receives
+ *             R_h * k * row_bytes bytes (2-byte aligned at least)
+ * ------------------------------------------------------------------------- */
+int taser_sample_temporal_rows(const taser_tcsr* g, const int32_t* roots, const int64_t* times,
+                               int64_t num_roots, int32_t k, int32_t hops, int32_t policy,
+                               uint64_t seed, int32_t m, const uint32_t* edge_weight,
+                               const void* table, int64_t table_rows, int32_t row_bytes, int64_t pitch_bytes,
+                               const taser_hop_out* out, void* const* rows_out, void* hip_stream);
 
 /* ---------------------------------------------------------------------------
  * Candidate-window products of the adaptive sampler (Sec. 3 overview, Alg. 1:

@@ -18,7 +18,7 @@ RECENT, UNIFORM, WEIGHTED, INVERSE_TIMESPAN = 0, 1, 2, 3
 INPUT_ON_DEVICE = 1
 MAX_K, MAX_M, MAX_HOPS = 64, 64, 3
 
-EXPORTS = ("taser_tcsr_build", "taser_tcsr_size", "taser_tcsr_view", "taser_tcsr_free", "taser_sample_temporal",
+EXPORTS = ("taser_tcsr_build", "taser_tcsr_size", "taser_tcsr_view", "taser_tcsr_free", "taser_sample_temporal", "taser_sample_temporal_rows",
            "taser_candidate_encodings", "taser_select_weighted", "taser_gather_features", "taser_cache_init", "taser_cache_lookup", "taser_cache_lookup_static", "taser_cache_prefetch", "taser_cache_gather", "taser_cache_tune", "taser_cache_count_accesses", "taser_cache_access_counts",
            "taser_cache_epoch_end", "taser_cache_residents",
            "taser_cache_free", "taser_selector_init", "taser_selector_draw", "taser_selector_update",
@@ -59,6 +59,8 @@ def lib():
         L.taser_tcsr_free.restype = None
         L.taser_sample_temporal.argtypes = [vp, vp, vp, i64, i32, i32, i32, u64, i32, vp,
                                             ctypes.POINTER(_HopOut), vp]
+        L.taser_sample_temporal_rows.argtypes = [vp, vp, vp, i64, i32, i32, i32, u64, i32, vp, vp, i64, i32, i64,
+                                                 ctypes.POINTER(_HopOut), ctypes.POINTER(vp), vp]
         L.taser_candidate_encodings.argtypes = [vp, vp, i64, i32, vp, vp, vp]
         L.taser_select_weighted.argtypes = [vp, vp, i64, i32, i32, u64, u32, vp, vp, ctypes.POINTER(_HopOut),
                                             ctypes.POINTER(_HopOut), vp]
@@ -171,24 +173,26 @@ def tcsr_free(g):
     g.free()
 
 
-def sample_temporal(g, roots, times, k, hops, policy, seed, m=0, edge_weight=None, out=None, stream=None):
-    """taser_sample_temporal. Returns a list of `hops` dicts of device tensors
-    nbr/eid/ts [R_h, k] and count [R_h] (allocated here unless `out` is given)."""
+def sample_outputs(n, k, hops, device):
+    """Freshly allocated output tensors of a `hops`-hop call on n roots."""
+    out, r = [], n
+    for _ in range(max(hops, 0)):
+        out.append(dict(nbr=torch.empty((r, k), dtype=torch.int32, device=device),
+                        eid=torch.empty((r, k), dtype=torch.int32, device=device),
+                        ts=torch.empty((r, k), dtype=torch.int64, device=device),
+                        count=torch.empty((r,), dtype=torch.int32, device=device)))
+        r *= k
+    return out
+
+
+def _hop_array(roots, times, n, k, edge_weight, out):
+    """Checks the sampler's tensors and packs the per-hop output pointers."""
     _want(roots, torch.int32, "roots")
     _want(times, torch.int64, "times")
     if edge_weight is not None:
         _want(edge_weight, torch.int32, "edge_weight (uint32 bits in an int32 tensor)")
-    n = roots.numel()
     if times.numel() != n:
         raise ValueError("roots and times must have the same length")
-    if out is None:
-        out, r = [], n
-        for _ in range(max(hops, 0)):
-            out.append(dict(nbr=torch.empty((r, k), dtype=torch.int32, device=roots.device),
-                            eid=torch.empty((r, k), dtype=torch.int32, device=roots.device),
-                            ts=torch.empty((r, k), dtype=torch.int64, device=roots.device),
-                            count=torch.empty((r,), dtype=torch.int32, device=roots.device)))
-            r *= k
     arr = (_HopOut * max(len(out), 1))()
     r = n
     for h, o in enumerate(out):
@@ -199,9 +203,47 @@ def sample_temporal(g, roots, times, k, hops, policy, seed, m=0, edge_weight=Non
                 raise ValueError(f"out[{h}].{name} is too small")
             setattr(arr[h], name, o[name].data_ptr())
         r *= k
+    return arr
+
+
+def sample_temporal(g, roots, times, k, hops, policy, seed, m=0, edge_weight=None, out=None, stream=None):
+    """taser_sample_temporal. Returns a list of `hops` dicts of device tensors
+    nbr/eid/ts [R_h, k] and count [R_h] (allocated here unless `out` is given)."""
+    n = roots.numel()
+    if out is None:
+        out = sample_outputs(n, k, hops, roots.device)
+    arr = _hop_array(roots, times, n, k, edge_weight, out)
     _check(lib().taser_sample_temporal(g.handle, _ptr(roots), _ptr(times), n, k, hops, policy, seed, m,
                                        _ptr(edge_weight), arr, _stream(stream)))
     return out
+
+
+def sample_temporal_rows(g, roots, times, k, hops, policy, seed, table, m=0, edge_weight=None, out=None, rows_out=None,
+                         row_elems=None, stream=None):
+    """taser_sample_temporal_rows: sample_temporal plus, per hop, the rows of `table`
+    (2-D device tensor with contiguous rows, as for gather_features) of the sampled edge
+    ids. Returns (out, rows_out); rows_out[h] is [R_h * k, d] of the table's dtype."""
+    if table.dim() != 2 or table.stride(1) != 1 or not table.is_cuda:
+        raise TypeError("table: expected a 2-D device tensor with contiguous rows")
+    n = roots.numel()
+    es = table.element_size()
+    d = table.shape[1] if row_elems is None else row_elems
+    if out is None:
+        out = sample_outputs(n, k, hops, roots.device)
+    if rows_out is None:
+        rows_out = [torch.empty((o["eid"].numel(), d), dtype=table.dtype, device=table.device) for o in out]
+    arr = _hop_array(roots, times, n, k, edge_weight, out)
+    ptrs = (ctypes.c_void_p * max(len(rows_out), 1))()
+    r = n
+    for h, t in enumerate(rows_out):
+        r *= k
+        if t.dtype != table.dtype or not t.is_contiguous() or t.numel() < r * d:
+            raise TypeError(f"rows_out[{h}]: expected a contiguous device tensor of the table's dtype with R_h*k*d elements")
+        ptrs[h] = t.data_ptr()
+    _check(lib().taser_sample_temporal_rows(g.handle, _ptr(roots), _ptr(times), n, k, hops, policy, seed, m,
+                                            _ptr(edge_weight), _ptr(table), table.shape[0], d * es, table.stride(0) * es,
+                                            arr, ptrs, _stream(stream)))
+    return out, rows_out
 
 
 def candidate_encodings(nbr, count, want_identity=True, stream=None):

@@ -23,6 +23,7 @@
 //     the whole valid list with a block per root (see its kernel).
 #include <mutex>
 
+#include "gather_kernel.h"
 #include "sampling_device.h"
 #include "taser_internal.h"
 
@@ -269,22 +270,125 @@ __device__ __forceinline__ void select_slots(
     }
 }
 
+// What a hop kernel needs to also write the feature rows of the edges it sampled
+// (Sec. 3.4 slices them right after Alg. 2 found the neighbors): the table, and the dense
+// output of this hop, one row per slot in slot order. The launcher guarantees: row_bytes a
+// multiple of 4 and >= 16, table and pitch 4-byte aligned, `out` 16-byte aligned, and the
+// rows of one wavefront's roots a multiple of 16 bytes.
+struct RowCopy {
+    const uint8_t* table;
+    int64_t table_rows, pitch_bytes;
+    uint8_t* out;
+    const uint8_t* zeros;    // 16 zero bytes
+    uint32_t row_bytes;
+    uint32_t magic;          // ceil(2^32 / row_bytes)
+    uint32_t step_rows, step_rest;   // 1024 = step_rows * row_bytes + step_rest
+};
+
+// The rows of one wavefront's roots form one contiguous, 16-byte aligned range of the
+// output: `rows_here` rows whose edge ids the wave has just left in `wave_eid` (LDS, slot
+// order). The range is copied as a flat stream, 16 bytes per lane and 1 KiB per wave
+// instruction, four of them in flight; a lane finds the row of its first chunk by one
+// division and of the following ones by stepping. A chunk inside one row is one 16-byte
+// load (4-byte aligned); one that crosses a row end takes two. Padding slots and ids
+// outside the table give zero rows.
+__device__ __forceinline__ void copy_wave_rows(const RowCopy& rc, const int32_t* wave_eid, uint32_t rows_here,
+                                               int64_t first_row, int lane) {
+    using namespace taser_gather;
+    const uint32_t bytes_here = rows_here * rc.row_bytes;
+    uint8_t* const out = rc.out + first_row * (int64_t)rc.row_bytes;
+    uint32_t o = (uint32_t)lane * 16u;
+    uint32_t row = __umulhi(o, rc.magic);
+    uint32_t off = o - row * rc.row_bytes;
+    constexpr int kInFlight = 4;
+    for (uint32_t base = 0; base < bytes_here; base += kInFlight * 1024u) {
+        uint32_t c_o[kInFlight], c_row[kInFlight], c_off[kInFlight];
+        bool whole[kInFlight], cross[kInFlight];
+#pragma unroll
+        for (int u = 0; u < kInFlight; ++u) {
+            c_o[u] = o;
+            c_row[u] = row;
+            c_off[u] = off;
+            const bool live = o < bytes_here;
+            whole[u] = live && off + 16u <= rc.row_bytes;
+            cross[u] = live && !whole[u];
+            o += 1024u;
+            row += rc.step_rows;
+            off += rc.step_rest;
+            if (off >= rc.row_bytes) {
+                off -= rc.row_bytes;
+                ++row;
+            }
+        }
+        u32x4 vals[kInFlight], tail[kInFlight], head[kInFlight];
+        uint32_t keep[kInFlight];   // dwords of a crossing chunk that belong to the row it starts in (1..3)
+#pragma unroll
+        for (int u = 0; u < kInFlight; ++u) {
+            const uint32_t r = c_row[u] < rows_here ? c_row[u] : rows_here - 1u;
+            const int32_t id = wave_eid[r];
+            const bool ok = id >= 0 && id < rc.table_rows;
+            const uint8_t* src = rc.table + (int64_t)(ok ? id : 0) * rc.pitch_bytes;
+            vals[u] = ((GlobalChunk16Ptr)(whole[u] && ok ? src + c_off[u] : rc.zeros))->v;
+            // A chunk that crosses a row end is the last dwords of this row followed by the first of
+            // the next one (rows hold at least 16 bytes): the last 16 bytes of the one and the first
+            // 16 of the other, read by the crossing lanes only and put together below.
+            keep[u] = (rc.row_bytes - c_off[u]) >> 2;
+            tail[u] = head[u] = u32x4{0u, 0u, 0u, 0u};
+            if (cross[u]) {
+                const int32_t id1 = r + 1u < rows_here ? wave_eid[r + 1u] : -1;   // past the range: never stored
+                const bool ok1 = id1 >= 0 && id1 < rc.table_rows;
+                tail[u] = ((GlobalChunk16Ptr)(ok ? src + (rc.row_bytes - 16u) : rc.zeros))->v;
+                head[u] = ((GlobalChunk16Ptr)(ok1 ? rc.table + (int64_t)id1 * rc.pitch_bytes : rc.zeros))->v;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kInFlight; ++u) {
+            // dwords 4 - keep .. 7 - keep of (tail, head), by selects in every lane
+            const u32x4 t = tail[u], h = head[u];
+            const bool k1 = keep[u] == 1u, k2 = keep[u] == 2u;
+            const uint32_t d0 = k1 ? t.w : k2 ? t.z : t.y;
+            const uint32_t d1 = k1 ? h.x : k2 ? t.w : t.z;
+            const uint32_t d2 = k1 ? h.y : k2 ? h.x : t.w;
+            const uint32_t d3 = k1 ? h.z : k2 ? h.y : h.x;
+            if (cross[u]) vals[u] = u32x4{d0, d1, d2, d3};
+        }
+#pragma unroll
+        for (int u = 0; u < kInFlight; ++u) {
+            if (c_o[u] + 16u <= bytes_here) {
+                __builtin_nontemporal_store(vals[u], reinterpret_cast<u32x4*>(out + c_o[u]));
+            } else if (c_o[u] < bytes_here) {
+                const uint32_t w[4] = {vals[u].x, vals[u].y, vals[u].z, vals[u].w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (c_o[u] + 4u * i < bytes_here) *reinterpret_cast<uint32_t*>(out + c_o[u] + 4u * i) = w[i];
+            }
+        }
+    }
+}
+
 // G lanes per root: G >= k, and G >= m for the weighted policy. A group serves
 // kRootsPerGroup consecutive roots: their searches run side by side, their selections
 // stage by stage (measured: two roots per group pay for the most-recent finder on large
 // hops, 39 -> 32 us for 120 000 roots; the uniform and weighted finders, whose time is
 // mostly the arithmetic of their draws, gain nothing from them).
-template <int POLICY, int G, int kRootsPerGroup>
+// With ROWS (one root per group) a wavefront then also copies the table rows of the edges
+// it sampled into the hop's dense row output: the finder is bound by instruction issue and
+// dependent reads, the copy by memory bandwidth, and in one kernel the wavefronts of a
+// compute unit that search overlap with those that copy.
+template <int POLICY, int G, int kRootsPerGroup, bool ROWS>
 __global__ __launch_bounds__(kThreads) void sample_hop_kernel(
     const int64_t* __restrict__ indptr, const TaserRec* __restrict__ rec, const TaserTimeIndex index,
     const int32_t* __restrict__ roots, const int64_t* __restrict__ times, int64_t num_roots,
     int32_t num_nodes, int k, uint32_t seed_lo, uint32_t seed_hi, uint32_t hop, int m, const uint32_t* __restrict__ edge_weight,
     int32_t* __restrict__ o_nbr, int32_t* __restrict__ o_eid, int64_t* __restrict__ o_ts,
-    int32_t* __restrict__ o_count) {
+    int32_t* __restrict__ o_count, const RowCopy rows) {
+    static_assert(!ROWS || kRootsPerGroup == 1, "the row copy takes one root per group");
     constexpr int kGroups = kWave / G;                         // groups per wave
     const int lane = threadIdx.x & (kWave - 1);
     const int group = lane / G, sub = lane % G;
-    const int64_t q0 = (((int64_t)blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6)) * kGroups + group) * kRootsPerGroup;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t wave_q0 = ((int64_t)blockIdx.x * (kThreads / kWave) + wave) * (kGroups * kRootsPerGroup);   // first root of the wave
+    const int64_t q0 = wave_q0 + group * kRootsPerGroup;
 
     uint32_t lo[kRootsPerGroup], hi[kRootsPerGroup], cnt[kRootsPerGroup];   // positions fit 32 bits: fewer than 2^31 entries
     int64_t t[kRootsPerGroup];
@@ -313,6 +417,17 @@ __global__ __launch_bounds__(kThreads) void sample_hop_kernel(
             if (sub < k) store_slot(o_nbr, o_eid, o_ts, (q0 + r) * k + sub, slot[r]);
             if (sub == 0) o_count[q0 + r] = filled[r];
         }
+    }
+    if (ROWS) {
+        __shared__ int32_t eid_of_row[kThreads / kWave][kWave];   // per wave: k ids per group, slot order (kGroups * k <= 64)
+        if (sub < k) eid_of_row[wave][group * k + sub] = slot[0].eid;
+        // only this wave reads them back: its LDS operations complete in order
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        int64_t roots_here = num_roots - wave_q0;
+        if (roots_here > kGroups) roots_here = kGroups;
+        if (roots_here > 0) copy_wave_rows(rows, eid_of_row[wave], (uint32_t)roots_here * (uint32_t)k, wave_q0 * k, lane);
     }
 }
 
@@ -535,74 +650,130 @@ int ensure_ts_only(const taser_tcsr* g_const, hipStream_t stream) {
     return TASER_OK;
 }
 
-template <int POLICY, int G, int kRootsPerGroup>
+template <int POLICY, int G, int kRootsPerGroup, bool ROWS>
 void launch_hop_gr(const taser_tcsr* g, const int32_t* roots, const int64_t* times, int64_t n, int k,
                    uint64_t seed, uint32_t hop, int m, const uint32_t* edge_weight, const taser_hop_out& o,
-                   hipStream_t stream) {
+                   const RowCopy& rows, hipStream_t stream) {
     constexpr int roots_per_block = (kThreads / kWave) * (kWave / G) * kRootsPerGroup;
     const unsigned grid = (unsigned)((n + roots_per_block - 1) / roots_per_block);
-    hipLaunchKernelGGL((sample_hop_kernel<POLICY, G, kRootsPerGroup>), dim3(grid), dim3(kThreads), 0, stream, g->indptr, g->rec, g->time_index,
+    hipLaunchKernelGGL((sample_hop_kernel<POLICY, G, kRootsPerGroup, ROWS>), dim3(grid), dim3(kThreads), 0, stream, g->indptr, g->rec, g->time_index,
                        roots, times, n, g->num_nodes, k, (uint32_t)seed, (uint32_t)(seed >> 32), hop, m, edge_weight, o.nbr,
-                       o.eid, o.ts, o.count);
+                       o.eid, o.ts, o.count, rows);
 }
 
 template <int POLICY, int G>
 void launch_hop_g(const taser_tcsr* g, const int32_t* roots, const int64_t* times, int64_t n, int k,
                   uint64_t seed, uint32_t hop, int m, const uint32_t* edge_weight, const taser_hop_out& o,
-                  hipStream_t stream) {
-    if (POLICY == TASER_RECENT && n >= 65536) launch_hop_gr<POLICY, G, 2>(g, roots, times, n, k, seed, hop, m, edge_weight, o, stream);
-    else launch_hop_gr<POLICY, G, 1>(g, roots, times, n, k, seed, hop, m, edge_weight, o, stream);
+                  const RowCopy* rows, hipStream_t stream) {
+    if (rows) launch_hop_gr<POLICY, G, 1, true>(g, roots, times, n, k, seed, hop, m, edge_weight, o, *rows, stream);
+    else if (POLICY == TASER_RECENT && n >= 65536) launch_hop_gr<POLICY, G, 2, false>(g, roots, times, n, k, seed, hop, m, edge_weight, o, RowCopy{}, stream);
+    else launch_hop_gr<POLICY, G, 1, false>(g, roots, times, n, k, seed, hop, m, edge_weight, o, RowCopy{}, stream);
+}
+
+// Lanes of a wavefront that serve one root.
+int group_lanes(int policy, int k, int m) {
+    const int lanes = (policy == TASER_WEIGHTED && m > k) ? m : k;   // lanes a root needs
+    return lanes <= 16 ? 16 : lanes <= 32 ? 32 : 64;
 }
 
 template <int POLICY>
 void launch_hop(const taser_tcsr* g, const int32_t* roots, const int64_t* times, int64_t n, int k,
                 uint64_t seed, uint32_t hop, int m, const uint32_t* edge_weight,
-                const taser_hop_out& o, hipStream_t stream) {
-    static const char* const names[3] = {"sample_hop_recent", "sample_hop_uniform", "sample_hop_weighted"};
-    TaserProfileSpan span(stream, names[POLICY]);
-    const int lanes = (POLICY == TASER_WEIGHTED && m > k) ? m : k;   // lanes a root needs
-    if (lanes <= 16) launch_hop_g<POLICY, 16>(g, roots, times, n, k, seed, hop, m, edge_weight, o, stream);
-    else if (lanes <= 32) launch_hop_g<POLICY, 32>(g, roots, times, n, k, seed, hop, m, edge_weight, o, stream);
-    else launch_hop_g<POLICY, 64>(g, roots, times, n, k, seed, hop, m, edge_weight, o, stream);
+                const taser_hop_out& o, const RowCopy* rows, hipStream_t stream) {
+    static const char* const names[2][3] = {{"sample_hop_recent", "sample_hop_uniform", "sample_hop_weighted"},
+                                            {"sample_rows_hop_recent", "sample_rows_hop_uniform", "sample_rows_hop_weighted"}};
+    TaserProfileSpan span(stream, names[rows ? 1 : 0][POLICY]);
+    const int lanes = group_lanes(POLICY, k, m);
+    if (lanes == 16) launch_hop_g<POLICY, 16>(g, roots, times, n, k, seed, hop, m, edge_weight, o, rows, stream);
+    else if (lanes == 32) launch_hop_g<POLICY, 32>(g, roots, times, n, k, seed, hop, m, edge_weight, o, rows, stream);
+    else launch_hop_g<POLICY, 64>(g, roots, times, n, k, seed, hop, m, edge_weight, o, rows, stream);
 }
 
-}  // namespace
+// The feature table a call wants sliced along with the sampling (null table: none).
+struct RowRequest {
+    const void* table;
+    int64_t table_rows;
+    int32_t row_bytes;
+    int64_t pitch_bytes;
+    void* const* out;   // per hop
+};
 
-extern "C" int taser_sample_temporal(const taser_tcsr* g, const int32_t* roots, const int64_t* times,
-                                     int64_t num_roots, int32_t k, int32_t hops, int32_t policy,
-                                     uint64_t seed, int32_t m, const uint32_t* edge_weight,
-                                     const taser_hop_out* out, void* hip_stream) {
-    if (!g || !out) return taser_fail(TASER_E_ARG, "sample_temporal: null graph or output array");
-    if (num_roots < 0) return taser_fail(TASER_E_ARG, "sample_temporal: num_roots = %lld", (long long)num_roots);
-    if (num_roots > 0 && (!roots || !times)) return taser_fail(TASER_E_ARG, "sample_temporal: null roots/times");
-    if (k < 1 || k > TASER_MAX_K) return taser_fail(TASER_E_RANGE, "sample_temporal: k = %d outside [1, %d]", k, TASER_MAX_K);
-    if (hops < 1 || hops > TASER_MAX_HOPS) return taser_fail(TASER_E_RANGE, "sample_temporal: hops = %d outside [1, %d]", hops, TASER_MAX_HOPS);
+int check_sampling_arguments(const char* what, const taser_tcsr* g, const int32_t* roots, const int64_t* times,
+                             int64_t num_roots, int32_t k, int32_t hops, int32_t policy, int32_t m,
+                             const uint32_t* edge_weight, const taser_hop_out* out) {
+    if (!g || !out) return taser_fail(TASER_E_ARG, "%s: null graph or output array", what);
+    if (num_roots < 0) return taser_fail(TASER_E_ARG, "%s: num_roots = %lld", what, (long long)num_roots);
+    if (num_roots > 0 && (!roots || !times)) return taser_fail(TASER_E_ARG, "%s: null roots/times", what);
+    if (k < 1 || k > TASER_MAX_K) return taser_fail(TASER_E_RANGE, "%s: k = %d outside [1, %d]", what, k, TASER_MAX_K);
+    if (hops < 1 || hops > TASER_MAX_HOPS) return taser_fail(TASER_E_RANGE, "%s: hops = %d outside [1, %d]", what, hops, TASER_MAX_HOPS);
     if (policy != TASER_RECENT && policy != TASER_UNIFORM && policy != TASER_WEIGHTED && policy != TASER_INVERSE_TIMESPAN)
-        return taser_fail(TASER_E_ARG, "sample_temporal: unknown policy %d", policy);
+        return taser_fail(TASER_E_ARG, "%s: unknown policy %d", what, policy);
     if (policy == TASER_WEIGHTED) {
-        if (m < 1 || m > TASER_MAX_M) return taser_fail(TASER_E_RANGE, "sample_temporal: m = %d outside [1, %d]", m, TASER_MAX_M);
-        if (!edge_weight) return taser_fail(TASER_E_ARG, "sample_temporal: weighted policy needs edge_weight");
+        if (m < 1 || m > TASER_MAX_M) return taser_fail(TASER_E_RANGE, "%s: m = %d outside [1, %d]", what, m, TASER_MAX_M);
+        if (!edge_weight) return taser_fail(TASER_E_ARG, "%s: weighted policy needs edge_weight", what);
     }
     int64_t n = num_roots;
     for (int h = 0; h < hops; ++h) {
         if (n > 0 && (!out[h].nbr || !out[h].eid || !out[h].ts || !out[h].count))
-            return taser_fail(TASER_E_ARG, "sample_temporal: null output buffer at hop %d", h);
-        if (n * k >= ((int64_t)1 << 31)) return taser_fail(TASER_E_RANGE, "sample_temporal: num_roots * k^hops must stay below 2^31");
+            return taser_fail(TASER_E_ARG, "%s: null output buffer at hop %d", what, h);
+        if (n * k >= ((int64_t)1 << 31)) return taser_fail(TASER_E_RANGE, "%s: num_roots * k^hops must stay below 2^31", what);
         n *= k;
     }
+    return TASER_OK;
+}
+
+// A wavefront copies the rows of its own roots only while they are few bytes: all wavefronts
+// of a launch search at the same time and then copy at the same time, so the two phases add up
+// instead of overlapping, and for long rows the plain gather (one launch for all hops) moves
+// the same bytes faster. Measured on 2 x 10 slots per root: up to 8 KiB per wavefront the hop
+// kernel's own copy is as fast or faster (64-byte rows: 44 against 50 us per batch of 4 000
+// roots, 25 against 29 us with 16 lanes per root), beyond it up to 15 % slower.
+constexpr int64_t kFinderCopyMaxWaveBytes = 8192;
+
+// All hops of one call. With `want`, hop h also leaves the table rows of its sampled edges in
+// want->out[h]: written by the hop kernel where the shapes allow it and the rows are short, else
+// by the plain gather launched after the last hop (same bytes either way), one launch for
+// consecutive hops whose edge ids and row buffers follow one another in memory.
+int sample_hops(const taser_tcsr* g, const int32_t* roots, const int64_t* times, int64_t num_roots, int32_t k,
+                int32_t hops, int32_t policy, uint64_t seed, int32_t m, const uint32_t* edge_weight,
+                const taser_hop_out* out, const RowRequest* want, hipStream_t stream) {
     taser_clear_stale_hip_error();
-    hipStream_t stream = (hipStream_t)hip_stream;
     if (policy == TASER_INVERSE_TIMESPAN) {
         const int rc = ensure_ts_only(g, stream);
         if (rc != TASER_OK) return rc;
     }
     const int32_t* cur_roots = roots;
     const int64_t* cur_times = times;
-    n = num_roots;
+    int64_t n = num_roots;
+    struct Pending {
+        const int32_t* ids;
+        int64_t n;
+        uint8_t* out;
+    } pending[TASER_MAX_HOPS];
+    int n_pending = 0;
     for (int h = 0; h < hops && n > 0; ++h) {
+        // Can this hop's kernel write the rows itself? It copies per wavefront, in aligned 16-byte
+        // pieces read at 4-byte alignment: rows, pitch and table must allow that, and the rows of
+        // one wavefront's roots must be whole 16-byte pieces.
+        RowCopy copy{};
+        const RowCopy* rows = nullptr;
+        if (want && policy != TASER_INVERSE_TIMESPAN) {
+            const int64_t wave_bytes = (int64_t)(kWave / group_lanes(policy, k, m)) * k * want->row_bytes;
+            const uint64_t bits = (uint64_t)want->row_bytes | (uint64_t)want->pitch_bytes | (uint64_t)(uintptr_t)want->table;
+            if (want->row_bytes >= 16 && wave_bytes <= kFinderCopyMaxWaveBytes && (bits & 3) == 0 && (wave_bytes & 15) == 0 &&
+                ((uintptr_t)want->out[h] & 15) == 0) {
+                const uint8_t* zeros = taser_gather::zero_chunk();
+                if (!zeros) return taser_fail(TASER_E_HIP, "sample_temporal_rows: the zero constant is not available on this device");
+                const uint32_t rb = (uint32_t)want->row_bytes;
+                copy = RowCopy{static_cast<const uint8_t*>(want->table), want->table_rows, want->pitch_bytes,
+                               static_cast<uint8_t*>(want->out[h]), zeros, rb, (uint32_t)((((uint64_t)1 << 32) + rb - 1) / rb),
+                               1024u / rb, 1024u % rb};
+                rows = &copy;
+            }
+        }
         switch (policy) {
-            case TASER_RECENT: launch_hop<TASER_RECENT>(g, cur_roots, cur_times, n, k, seed, (uint32_t)h, m, edge_weight, out[h], stream); break;
-            case TASER_UNIFORM: launch_hop<TASER_UNIFORM>(g, cur_roots, cur_times, n, k, seed, (uint32_t)h, m, edge_weight, out[h], stream); break;
+            case TASER_RECENT: launch_hop<TASER_RECENT>(g, cur_roots, cur_times, n, k, seed, (uint32_t)h, m, edge_weight, out[h], rows, stream); break;
+            case TASER_UNIFORM: launch_hop<TASER_UNIFORM>(g, cur_roots, cur_times, n, k, seed, (uint32_t)h, m, edge_weight, out[h], rows, stream); break;
             case TASER_INVERSE_TIMESPAN: {
                 TaserProfileSpan span(stream, "sample_hop_inverse_timespan");
                 const unsigned grid = (unsigned)n;   // one block per root (n < 2^31)
@@ -611,12 +782,58 @@ extern "C" int taser_sample_temporal(const taser_tcsr* g, const int32_t* roots, 
                                    (uint32_t)h, out[h].nbr, out[h].eid, out[h].ts, out[h].count);
                 break;
             }
-            default: launch_hop<TASER_WEIGHTED>(g, cur_roots, cur_times, n, k, seed, (uint32_t)h, m, edge_weight, out[h], stream); break;
+            default: launch_hop<TASER_WEIGHTED>(g, cur_roots, cur_times, n, k, seed, (uint32_t)h, m, edge_weight, out[h], rows, stream); break;
+        }
+        if (want && !rows) {
+            uint8_t* to = static_cast<uint8_t*>(want->out[h]);
+            Pending* last = n_pending ? &pending[n_pending - 1] : nullptr;
+            if (last && last->ids + last->n == out[h].eid && last->out + last->n * want->row_bytes == to) last->n += n * k;
+            else pending[n_pending++] = Pending{out[h].eid, n * k, to};
         }
         cur_roots = out[h].nbr;
         cur_times = out[h].ts;
         n *= k;
     }
     TASER_HIP_TRY(hipGetLastError());
+    for (int i = 0; i < n_pending; ++i) {
+        const int rc = taser_launch_gather(want->table, want->table_rows, want->row_bytes, want->pitch_bytes, pending[i].ids, pending[i].n,
+                                           pending[i].out, stream);
+        if (rc != TASER_OK) return rc;
+    }
     return TASER_OK;
+}
+
+}  // namespace
+
+extern "C" int taser_sample_temporal(const taser_tcsr* g, const int32_t* roots, const int64_t* times,
+                                     int64_t num_roots, int32_t k, int32_t hops, int32_t policy,
+                                     uint64_t seed, int32_t m, const uint32_t* edge_weight,
+                                     const taser_hop_out* out, void* hip_stream) {
+    const int rc = check_sampling_arguments("sample_temporal", g, roots, times, num_roots, k, hops, policy, m, edge_weight, out);
+    if (rc != TASER_OK) return rc;
+    return sample_hops(g, roots, times, num_roots, k, hops, policy, seed, m, edge_weight, out, nullptr, (hipStream_t)hip_stream);
+}
+
+extern "C" int taser_sample_temporal_rows(const taser_tcsr* g, const int32_t* roots, const int64_t* times,
+                                          int64_t num_roots, int32_t k, int32_t hops, int32_t policy,
+                                          uint64_t seed, int32_t m, const uint32_t* edge_weight,
+                                          const void* table, int64_t table_rows, int32_t row_bytes, int64_t pitch_bytes,
+                                          const taser_hop_out* out, void* const* rows_out, void* hip_stream) {
+    const char* what = "sample_temporal_rows";
+    const int rc = check_sampling_arguments(what, g, roots, times, num_roots, k, hops, policy, m, edge_weight, out);
+    if (rc != TASER_OK) return rc;
+    if (table_rows < 0) return taser_fail(TASER_E_ARG, "%s: negative table_rows", what);
+    if (row_bytes <= 0 || (row_bytes & 1)) return taser_fail(TASER_E_ARG, "%s: row_bytes = %d must be positive and even", what, row_bytes);
+    if (pitch_bytes < row_bytes || (pitch_bytes & 1)) return taser_fail(TASER_E_ARG, "%s: pitch_bytes = %lld must be even and >= row_bytes", what, (long long)pitch_bytes);
+    if (!table && table_rows > 0) return taser_fail(TASER_E_ARG, "%s: null table", what);
+    if ((uintptr_t)table & 1) return taser_fail(TASER_E_ARG, "%s: table must be 2-byte aligned", what);
+    if (!rows_out) return taser_fail(TASER_E_ARG, "%s: null rows_out", what);
+    int64_t n = num_roots;
+    for (int h = 0; h < hops; ++h) {
+        if (n > 0 && !rows_out[h]) return taser_fail(TASER_E_ARG, "%s: null row buffer at hop %d", what, h);
+        if ((uintptr_t)rows_out[h] & 1) return taser_fail(TASER_E_ARG, "%s: row buffers must be 2-byte aligned", what);
+        n *= k;
+    }
+    const RowRequest want{table, table_rows, row_bytes, pitch_bytes, rows_out};
+    return sample_hops(g, roots, times, num_roots, k, hops, policy, seed, m, edge_weight, out, &want, (hipStream_t)hip_stream);
 }

@@ -426,6 +426,91 @@ def test_adaptive_two_hop_pipeline_on_the_flights_shaped_workload():
         ref_roots, ref_times = fused[hop]["nbr"].ravel(), fused[hop]["ts"].ravel()
 
 
+# ----------------------------------------------------------------------------- sampling with the rows in one call
+def check_rows_call(g, g_ref, roots, times, k, hops, policy, seed, table_np, table_dev, m=0, weight=None, table_rows=None):
+    """taser_sample_temporal_rows against the oracle's finder followed by the oracle's gather;
+    the row buffers carry guard elements behind the last row."""
+    want = oracle.sample_temporal(g_ref, roots, times, k, hops, policy, seed, m, weight, THREADS)
+    d = table_np.shape[1]
+    guard = 64
+    bufs, r = [], roots.shape[0]
+    for _ in range(hops):
+        r *= k
+        bufs.append(torch.full((r * d + guard,), 77, dtype=table_dev.dtype, device="cuda"))
+    w_dev = None if weight is None else dev(weight.view(np.int32))
+    t_dev = table_dev if table_rows is None else table_dev[:table_rows]
+    got, rows = T.sample_temporal_rows(g, dev(roots), dev(times), k, hops, policy, seed, t_dev, m=m, edge_weight=w_dev,
+                                       rows_out=bufs, row_elems=d)
+    torch.cuda.synchronize()
+    assert_hops_equal(got, want)
+    for h in range(hops):
+        ids = want[h]["eid"].ravel().copy()
+        if table_rows is not None:
+            ids[ids >= table_rows] = -1
+        ref = oracle.gather(table_np, ids, threads=THREADS)
+        out = rows[h].cpu().numpy()
+        a, b = out[:ids.shape[0] * d].view(np.uint8), ref.ravel().view(np.uint8)
+        if a.tobytes() != b.tobytes():
+            at = int(np.flatnonzero(a != b)[0])
+            rb = d * table_np.itemsize
+            raise AssertionError(f"rows of hop {h}: {int((a != b).sum())} bytes differ, the first in row {at // rb} "
+                                 f"(id {ids[at // rb]}) at byte {at % rb} of {rb}")
+        assert (out[ids.shape[0] * d:] == 77).all(), f"guard behind hop {h}"
+
+
+@pytest.mark.parametrize("policy", [T.RECENT, T.UNIFORM, T.WEIGHTED, T.INVERSE_TIMESPAN])
+@pytest.mark.parametrize("k,m,dtype,dim,pad,offset", [
+    (10, 25, np.float16, 172, 0, 0),     # 344-byte rows: every other row starts 8 bytes off a 16-byte boundary
+    (10, 25, np.float16, 186, 6, 0),     # 372 bytes at a 384-byte pitch
+    (7, 5, np.float16, 186, 0, 0),       # a last wavefront whose rows end inside a 16-byte piece
+    (10, 12, np.float32, 16, 0, 0),      # 64-byte rows: sixteen rows per wave instruction
+    (10, 25, np.float32, 413, 0, 0),     # 1652 bytes: too many bytes per wavefront for the hop kernel -> gather launch
+    (32, 64, np.float32, 4, 0, 0),       # 16-byte rows, the shortest the hop kernel copies itself
+    (1, 2, np.float32, 500, 0, 0),       # 2000-byte rows, one slot per root: rows longer than a wave instruction, copied by the hop kernel
+    (2, 2, np.float32, 413, 0, 0),       # 1652-byte rows of two slots: beyond what the hop kernel copies itself -> gather launch
+    (1, 2, np.float32, 5, 3, 0),         # one slot per root, 20-byte rows
+    (64, 64, np.float16, 172, 0, 0),     # one root per wavefront, 22 KB of rows -> gather launch
+    (64, 64, np.float16, 62, 0, 0),      # one root per wavefront, 124-byte rows
+    (3, 40, np.float16, 10, 0, 0),       # 20-byte rows of three slots: a wavefront's rows are not whole 16-byte pieces -> two launches
+    (10, 25, np.float16, 7, 0, 0),       # 14-byte rows -> two launches
+    (10, 25, np.float16, 9, 3, 1),       # odd pitch, table starting 2 bytes into an allocation -> two launches
+])
+def test_sampling_with_rows_equals_the_oracle(policy, k, m, dtype, dim, pad, offset):
+    rng = np.random.default_rng(1000 * k + dim)
+    n_nodes, n = 60, 30000
+    src, dst, ts, eid = _graph(rng, n_nodes, n, 4000)
+    src = np.minimum(src, rng.integers(0, n_nodes, n)).astype(np.int32)     # skewed degrees, some empty lists
+    src[src == 7] = 8
+    g, g_ref = build_both(src, dst, ts, eid, n_nodes)
+    weight = rng.integers(1, 1 << 16, n).astype(np.uint32)
+    full = rng.standard_normal((n, dim + pad + offset)).astype(dtype)
+    table = full[:, offset:offset + dim]
+    table_dev = dev(full)[:, offset:offset + dim]
+    hops = 3 if k <= 7 else (2 if k <= 10 else 1)
+    for n_roots in (333, 1, 64):
+        roots = rng.integers(0, n_nodes, n_roots).astype(np.int32)
+        roots[::50] = -1
+        times = rng.integers(-5, 4100, n_roots).astype(np.int64)
+        check_rows_call(g, g_ref, roots, times, k, hops, policy, 0xABCDEF0123456789, table, table_dev, m=m, weight=weight)
+    # a table that ends before the largest edge id: zero rows beyond it
+    roots = rng.integers(0, n_nodes, 100).astype(np.int32)
+    times = rng.integers(2000, 4100, 100).astype(np.int64)
+    check_rows_call(g, g_ref, roots, times, k, 1, policy, 5, table, table_dev, m=m, weight=weight, table_rows=n // 2)
+
+
+def test_sampling_with_rows_on_the_reddit_and_flights_shaped_workloads():
+    w = W.make(3, num_batches=2)
+    g, g_ref = build_both(w.src, w.dst, w.ts, w.eid, w.num_nodes)
+    table = dev(w.edge_feat)
+    for roots, times in w.batches:
+        check_rows_call(g, g_ref, roots, times, w.k, 2, W.UNIFORM, 42, w.edge_feat, table)
+    w = W.make(4, num_batches=2)
+    g, g_ref = build_both(w.src, w.dst, w.ts, w.eid, w.num_nodes)
+    table = dev(w.edge_feat)
+    for roots, times in w.batches:
+        check_rows_call(g, g_ref, roots, times, w.k, 2, W.WEIGHTED, 42, w.edge_feat, table, m=w.m, weight=w.edge_weight)
+
+
 # ----------------------------------------------------------------------------- gather edge cases
 @pytest.mark.parametrize("dtype,dim,pad,offset", [
     (np.float32, 16, 0, 0),      # 64-byte rows, 16-byte vectors

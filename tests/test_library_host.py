@@ -66,6 +66,23 @@ def test_argument_errors_are_reported_without_a_gpu():
         setattr(big[0], f, 8)
     assert lib.taser_sample_temporal(g, one, one, 2 ** 28, 10, 1, 0, 0, 0, None, big, None) == E_RANGE
 
+    # the same finder with the rows of a table: the sampler's checks first, then the gather's
+    vp = ctypes.c_void_p
+    rows = (vp * 1)(16)
+    tbl = (vp(16), 4, 64, 64)     # table, table_rows, row_bytes, pitch_bytes
+    assert lib.taser_sample_temporal_rows(None, one, one, 1, 10, 1, 0, 0, 0, None, *tbl, big, rows, None) == E_ARG
+    assert lib.taser_sample_temporal_rows(g, one, one, 1, 65, 1, 0, 0, 0, None, *tbl, big, rows, None) == E_RANGE
+    assert lib.taser_sample_temporal_rows(g, one, one, 1, 10, 1, 2, 0, 25, None, *tbl, big, rows, None) == E_ARG      # no weights
+    assert lib.taser_sample_temporal_rows(g, one, one, 1, 10, 1, 0, 0, 0, None, vp(16), -1, 64, 64, big, rows, None) == E_ARG
+    assert lib.taser_sample_temporal_rows(g, one, one, 1, 10, 1, 0, 0, 0, None, vp(16), 4, 0, 64, big, rows, None) == E_ARG
+    assert lib.taser_sample_temporal_rows(g, one, one, 1, 10, 1, 0, 0, 0, None, vp(16), 4, 15, 64, big, rows, None) == E_ARG
+    assert lib.taser_sample_temporal_rows(g, one, one, 1, 10, 1, 0, 0, 0, None, vp(16), 4, 64, 32, big, rows, None) == E_ARG
+    assert lib.taser_sample_temporal_rows(g, one, one, 1, 10, 1, 0, 0, 0, None, None, 4, 64, 64, big, rows, None) == E_ARG
+    assert lib.taser_sample_temporal_rows(g, one, one, 1, 10, 1, 0, 0, 0, None, vp(17), 4, 64, 64, big, rows, None) == E_ARG
+    assert lib.taser_sample_temporal_rows(g, one, one, 1, 10, 1, 0, 0, 0, None, *tbl, big, None, None) == E_ARG
+    assert lib.taser_sample_temporal_rows(g, one, one, 1, 10, 1, 0, 0, 0, None, *tbl, big, (vp * 1)(None), None) == E_ARG
+    assert lib.taser_sample_temporal_rows(g, one, one, 1, 10, 1, 0, 0, 0, None, *tbl, big, (vp * 1)(17), None) == E_ARG
+
     assert lib.taser_candidate_encodings(one, one, -1, 25, one, one, None) == E_ARG
     assert lib.taser_candidate_encodings(one, one, 4, 0, one, one, None) == E_RANGE
     assert lib.taser_candidate_encodings(one, one, 4, 65, one, one, None) == E_RANGE
