@@ -52,13 +52,22 @@ __device__ __forceinline__ int64_t item_index(int64_t tile0, int wave, int r, in
 // [2] / [3]: OR / AND of the biased timestamps (bytes in which they agree need no
 // sorting pass). fold_info_kernel combines the per-block words (atomics from every
 // block onto four shared words took longer than reading the input).
+// The block also counts its tile's node ids by their lowest digit, hist[bin * num_blocks +
+// tile] as radix_hist_kernel would: time-sorted input (the usual case) is sorted by the node
+// digits only, lowest first, and that pass then needs no histogram kernel of its own (the
+// counting hides behind this kernel's memory traffic).
 __global__ __launch_bounds__(kThreads) void pack_inspect_kernel(const int32_t* __restrict__ src,
                                                                 const int32_t* __restrict__ dst,
                                                                 const int64_t* __restrict__ ts,
                                                                 const int32_t* __restrict__ eid, int64_t n,
                                                                 int32_t num_nodes, TaserRec* __restrict__ rec,
                                                                 int32_t* __restrict__ key,
-                                                                unsigned long long* __restrict__ partial) {
+                                                                unsigned long long* __restrict__ partial,
+                                                                uint32_t low_digit_mask, uint32_t* __restrict__ hist,
+                                                                uint32_t num_blocks) {
+    __shared__ uint32_t bins[kBins];
+    bins[threadIdx.x] = 0;
+    __syncthreads();
     unsigned long long any_or = 0, all_and = ~0ull;
     int bad = 0, unsorted = 0;
     constexpr int kPer = 4;   // entries per thread and round: their loads are issued together
@@ -92,6 +101,7 @@ __global__ __launch_bounds__(kThreads) void pack_inspect_kernel(const int32_t* _
             r.eid = e[u];
             rec[i] = r;
             key[i] = s[u];
+            atomicAdd(&bins[(uint32_t)s[u] & low_digit_mask], 1u);
         }
     }
     for (int d = 1; d < kWave; d <<= 1) {
@@ -109,6 +119,7 @@ __global__ __launch_bounds__(kThreads) void pack_inspect_kernel(const int32_t* _
         w_unsorted[wave] = any_unsorted != 0;
     }
     __syncthreads();
+    if (hist) hist[(size_t)threadIdx.x * num_blocks + blockIdx.x] = bins[threadIdx.x];
     if (threadIdx.x == 0) {
         unsigned long long o = 0, a = ~0ull;
         int b = 0, u = 0;
@@ -212,12 +223,13 @@ __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const TaserRec* __
 // a slice takes the items whose place falls into it): a whole tile of records
 // and keys, 80 KB, would leave room for one block per compute unit, a slice of
 // half a tile for three, which is what the registers allow.
+// `level1` (last pass only, else null): see the write-out.
 constexpr int kParts = 2;
 constexpr int kPart = kTile / kParts;
 __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
     const TaserRec* __restrict__ rec_in, const int32_t* __restrict__ key_in, int64_t n, DigitSpec d,
     const uint32_t* __restrict__ offs, uint32_t num_blocks, TaserRec* __restrict__ rec_out,
-    int32_t* __restrict__ key_out) {
+    int32_t* __restrict__ key_out, int64_t* __restrict__ level1) {
     __shared__ uint32_t wave_count[kWaves][kBins];   // items of each wave per digit, then exclusive over waves
     __shared__ uint32_t block_base[kBins];           // global position of the block's first item of a digit
     __shared__ uint32_t local_base[kBins];           // position of that item inside the ordered tile
@@ -315,6 +327,9 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
                 const uint32_t to = block_base[dg] + (part0 + j - local_base[dg]);
                 rec_out[to] = rr;
                 key_out[to] = kk;
+                // the last pass knows the final positions: it also leaves level 1 of the search index
+                // (the timestamp of the last record of every run of 16, and of the array's last record)
+                if (level1 && ((to & 15u) == 15u || (int64_t)to == n - 1)) level1[to >> 4] = rr.ts;
             }
         }
         __syncthreads();   // the slice is free again
@@ -425,6 +440,12 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
     TASER_HIP_TRY(rec_a.alloc(n * sizeof(TaserRec)));
     TASER_HIP_TRY(key_a.alloc(n * sizeof(int32_t)));
     unsigned long long info[4] = {0, 0, 0, ~0ull};
+    int node_bits = 0;
+    while (((int64_t)1 << node_bits) < (int64_t)num_nodes) ++node_bits;
+    const uint32_t num_blocks = blocks_for(n, kTile);
+    const int64_t hist_len = (int64_t)kBins * num_blocks;
+    const uint32_t low_digit_mask = (1u << (node_bits < 8 ? node_bits : 8)) - 1u;
+    if (n > 0) TASER_HIP_TRY(hist.alloc(hist_len * sizeof(uint32_t)));
     if (n > 0) {
         const unsigned grid = blocks_for(n, kTile);
         constexpr unsigned kFoldBlocks = 128;
@@ -435,7 +456,8 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
         {
             TaserProfileSpan span(stream, "tcsr_pack_inspect");
             hipLaunchKernelGGL(pack_inspect_kernel, dim3(grid), dim3(kThreads), 0, stream, src, dst, ts, eid, n, num_nodes,
-                               rec_a.as<TaserRec>(), key_a.as<int32_t>(), d_partial.as<unsigned long long>());
+                               rec_a.as<TaserRec>(), key_a.as<int32_t>(), d_partial.as<unsigned long long>(), low_digit_mask,
+                               hist.as<uint32_t>(), num_blocks);
             hipLaunchKernelGGL(fold_info_kernel, dim3(kFoldBlocks), dim3(kThreads), 0, stream,
                                d_partial.as<unsigned long long>(), grid, d_folded.as<unsigned long long>());
             hipLaunchKernelGGL(fold_info_kernel, dim3(1), dim3(kThreads), 0, stream, d_folded.as<unsigned long long>(),
@@ -452,51 +474,13 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
         for (int b = 0; b < 8; ++b)
             if ((differ >> (8 * b)) & 0xffull) passes.push_back(DigitSpec{1, 8 * b, 0xffu});
     }
-    int node_bits = 0;
-    while (((int64_t)1 << node_bits) < (int64_t)num_nodes) ++node_bits;
+    const bool first_hist_known = passes.empty();   // no timestamp passes: the first digit is the one pack_inspect_kernel counted
     for (int shift = 0; shift < node_bits; shift += 8) {
         const int width = node_bits - shift < 8 ? node_bits - shift : 8;
         passes.push_back(DigitSpec{0, shift, (1u << width) - 1u});
     }
 
-    // ---- one stable pass per digit, ping-pong between two buffers
-    TASER_HIP_TRY(indptr.alloc(((size_t)num_nodes + 1) * sizeof(int64_t)));
-    const uint32_t num_blocks = blocks_for(n, kTile);
-    const int64_t hist_len = (int64_t)kBins * num_blocks;
-    const unsigned scan_blocks = taser_scan::num_partials(hist_len);
-    if (n > 0) {
-        if (!passes.empty()) {
-            TASER_HIP_TRY(rec_b.alloc(n * sizeof(TaserRec)));
-            TASER_HIP_TRY(key_b.alloc(n * sizeof(int32_t)));
-            TASER_HIP_TRY(hist.alloc(hist_len * sizeof(uint32_t)));
-            TASER_HIP_TRY(partial.alloc((size_t)scan_blocks * sizeof(uint32_t)));
-        }
-        for (const DigitSpec& d : passes) {
-            {
-                TaserProfileSpan span(stream, "tcsr_radix_hist");
-                hipLaunchKernelGGL(radix_hist_kernel, dim3(num_blocks), dim3(kThreads), 0, stream,
-                                   rec_a.as<TaserRec>(), key_a.as<int32_t>(), n, d, hist.as<uint32_t>(), num_blocks);
-            }
-            {
-                TaserProfileSpan span(stream, "tcsr_scan");
-                taser_scan::exclusive_scan_u32(hist.as<uint32_t>(), hist_len, partial.as<uint32_t>(), stream);
-            }
-            {
-                TaserProfileSpan span(stream, "tcsr_radix_scatter");
-                hipLaunchKernelGGL(radix_scatter_kernel, dim3(pass_grid(num_blocks)), dim3(kThreads), 0, stream,
-                                   rec_a.as<TaserRec>(), key_a.as<int32_t>(), n, d, hist.as<uint32_t>(), num_blocks,
-                                   rec_b.as<TaserRec>(), key_b.as<int32_t>());
-            }
-            void* t = rec_a.p; rec_a.p = rec_b.p; rec_b.p = t;
-            t = key_a.p; key_a.p = key_b.p; key_b.p = t;
-        }
-    }
-    {
-        TaserProfileSpan span(stream, "tcsr_indptr");
-        hipLaunchKernelGGL(indptr_kernel, dim3(blocks_for(n + 1, kThreads * 4)), dim3(kThreads), 0, stream,
-                           key_a.as<int32_t>(), n, num_nodes, indptr.as<int64_t>());
-    }
-    // ---- search index over the sorted timestamps
+    // ---- search index over the sorted timestamps: storage (level 1 is written by the last sorting pass)
     TaserTimeIndex index = {};
     index.num_entries = n;
     int64_t index_total = 0, level_at[kTimeIndexLevels];
@@ -509,10 +493,47 @@ extern "C" int taser_tcsr_build(const int32_t* src, const int32_t* dst, const in
     DevBuf index_storage;
     TASER_HIP_TRY(index_storage.alloc((size_t)(index_total > 0 ? index_total : 1) * sizeof(int64_t)));
     for (int l = 0; l < kTimeIndexLevels; ++l) index.level[l] = index_storage.as<int64_t>() + level_at[l];
+    // ---- one stable pass per digit, ping-pong between two buffers
+    TASER_HIP_TRY(indptr.alloc(((size_t)num_nodes + 1) * sizeof(int64_t)));
+    const unsigned scan_blocks = taser_scan::num_partials(hist_len);
+    if (n > 0) {
+        if (!passes.empty()) {
+            TASER_HIP_TRY(rec_b.alloc(n * sizeof(TaserRec)));
+            TASER_HIP_TRY(key_b.alloc(n * sizeof(int32_t)));
+            TASER_HIP_TRY(partial.alloc((size_t)scan_blocks * sizeof(uint32_t)));
+        }
+        for (size_t pass = 0; pass < passes.size(); ++pass) {
+            const DigitSpec& d = passes[pass];
+            if (pass > 0 || !first_hist_known) {
+                TaserProfileSpan span(stream, "tcsr_radix_hist");
+                hipLaunchKernelGGL(radix_hist_kernel, dim3(num_blocks), dim3(kThreads), 0, stream,
+                                   rec_a.as<TaserRec>(), key_a.as<int32_t>(), n, d, hist.as<uint32_t>(), num_blocks);
+            }
+            {
+                TaserProfileSpan span(stream, "tcsr_scan");
+                taser_scan::exclusive_scan_u32(hist.as<uint32_t>(), hist_len, partial.as<uint32_t>(), stream);
+            }
+            {
+                TaserProfileSpan span(stream, "tcsr_radix_scatter");
+                hipLaunchKernelGGL(radix_scatter_kernel, dim3(pass_grid(num_blocks)), dim3(kThreads), 0, stream,
+                                   rec_a.as<TaserRec>(), key_a.as<int32_t>(), n, d, hist.as<uint32_t>(), num_blocks,
+                                   rec_b.as<TaserRec>(), key_b.as<int32_t>(),
+                                   pass + 1 == passes.size() ? index_storage.as<int64_t>() + level_at[0] : nullptr);
+            }
+            void* t = rec_a.p; rec_a.p = rec_b.p; rec_b.p = t;
+            t = key_a.p; key_a.p = key_b.p; key_b.p = t;
+        }
+    }
+    {
+        TaserProfileSpan span(stream, "tcsr_indptr");
+        hipLaunchKernelGGL(indptr_kernel, dim3(blocks_for(n + 1, kThreads * 4)), dim3(kThreads), 0, stream,
+                           key_a.as<int32_t>(), n, num_nodes, indptr.as<int64_t>());
+    }
     if (n > 0) {
         TaserProfileSpan span(stream, "tcsr_time_index");
-        hipLaunchKernelGGL(time_index_first_kernel, dim3(blocks_for(index.len[0], kThreads)), dim3(kThreads), 0, stream,
-                           rec_a.as<TaserRec>(), n, index_storage.as<int64_t>() + level_at[0], index.len[0]);
+        if (passes.empty())   // nothing was sorted: level 1 from the records as they are
+            hipLaunchKernelGGL(time_index_first_kernel, dim3(blocks_for(index.len[0], kThreads)), dim3(kThreads), 0, stream,
+                               rec_a.as<TaserRec>(), n, index_storage.as<int64_t>() + level_at[0], index.len[0]);
         for (int l = 1; l < kTimeIndexLevels; ++l)
             hipLaunchKernelGGL(time_index_next_kernel, dim3(blocks_for(index.len[l], kThreads)), dim3(kThreads), 0, stream,
                                index.level[l - 1], index.len[l - 1], index_storage.as<int64_t>() + level_at[l],
