@@ -283,6 +283,34 @@ def test_sampler_is_deterministic_and_independent_of_batch_split():
     assert torch.equal(a[0]["count"], c[0]["count"])
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_graphs_all_policies(seed):
+    """Randomly shaped small graphs (node count, size, time span, sorted or not, degree skew), random
+    k, m, hops, root counts around the wave and block sizes: the whole path, build included."""
+    rng = np.random.default_rng(9000 + seed)
+    n_nodes = int(rng.choice([1, 2, 3, 17, 200, 5000]))
+    n = int(rng.choice([1, 50, 700, 5000, 40000]))
+    span = int(rng.choice([1, 3, 100, 100000, 1 << 40]))
+    src, dst, ts, eid = _graph(rng, n_nodes, n, span, sorted_ts=bool(rng.integers(0, 2)), lo=int(rng.choice([0, -span // 2, -(1 << 50)])))
+    if rng.integers(0, 2):
+        src = np.minimum(src, rng.integers(0, n_nodes, n)).astype(np.int32)
+    g, g_ref = build_both(src, dst, ts, eid, n_nodes)
+    assert_tcsr_equal(g, g_ref)
+    weight = rng.integers(1, int(rng.choice([2, 1 << 16, (1 << 32) - 1])), n, dtype=np.int64).astype(np.uint32)
+    dim = int(rng.choice([4, 6, 16, 43]))
+    table = rng.standard_normal((n, dim)).astype(np.float32)
+    table_dev = dev(table)
+    for _ in range(3):
+        k = int(rng.choice([1, 2, 5, 10, 16, 17, 32, 33, 64]))
+        m = int(rng.integers(1, 65))
+        hops = 3 if k <= 5 else (2 if k <= 10 else 1)
+        n_roots = int(rng.choice([1, 3, 4, 5, 63, 64, 65, 255, 257, 1000]))
+        roots = rng.integers(-1, n_nodes, n_roots).astype(np.int32)                # some negative (roots without neighbors)
+        times = rng.integers(int(ts.min()) - 2, int(ts.max()) + 3, n_roots).astype(np.int64)
+        for policy in (T.RECENT, T.UNIFORM, T.WEIGHTED, T.INVERSE_TIMESPAN):
+            check_rows_call(g, g_ref, roots, times, k, hops, policy, int(rng.integers(0, 1 << 62)), table, table_dev, m=m, weight=weight)
+
+
 # ----------------------------------------------------------------------------- inverse-timespan finder
 @pytest.mark.parametrize("k", [1, 10, 64])
 def test_inverse_timespan_matches_the_oracle(k):
