@@ -629,6 +629,54 @@ def test_cache_partitioned_gather_equals_the_oracle(dim, n):
         T.cache_epoch_end(c, min_overlap=cap if epoch == 0 else 0)     # marks hot rows (and swaps the content once)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_cache_random_shapes(seed):
+    """Random table shapes (row lengths on both sides of every kernel's limits, fp16 and fp32, padded
+    pitch), capacities, staging sizes, request counts and skews; every gather mode, the
+    allocation-free lookup, hit/miss counts, access counters and one epoch end in between."""
+    rng = np.random.default_rng(31000 + seed)
+    rows = int(rng.choice([1, 7, 300, 2000, 9000]))
+    dtype = [np.float16, np.float32][int(rng.integers(0, 2))]
+    dim = int(rng.choice([1, 2, 3, 8, 31, 64, 127, 128, 129, 256, 413, 1025]))
+    pad = int(rng.choice([0, 0, 1, 5]))
+    if dtype is np.float16:
+        dim, pad = 2 * dim, 2 * pad                                  # the cache wants rows and pitch in whole 4-byte words
+    full = torch.from_numpy(rng.standard_normal((rows, dim + pad)).astype(dtype)).pin_memory()
+    host = full[:, :dim]
+    cap = int(rng.choice([0, 1, rows // 5, rows // 2, rows]))
+    staging = int(rng.choice([0, 3, rows // 3, rows]))
+    residents = torch.from_numpy(rng.permutation(rows)[:cap].astype(np.int32)) if rng.integers(0, 2) else None
+    c = T.cache_init(host, cap, residents, seed=seed, staging_rows=staging)
+    res = T.cache_residents(c).numpy()
+    T.cache_count_accesses(c)
+    Q = np.zeros(rows, np.uint32)
+    for call in range(4):
+        n = int(rng.choice([1, 63, 500, 4096, 4097, 30000]))
+        a = float(rng.choice([1.05, 1.5, 3.0]))
+        ids_np = ((rng.zipf(a, n) - 1) % rows).astype(np.int32) if rng.integers(0, 2) else rng.integers(0, rows, n).astype(np.int32)
+        ids_np[::13] = -1
+        ids = dev(ids_np)
+        want = oracle.gather(host.numpy(), ids_np, threads=THREADS).tobytes()
+        hm = torch.zeros(2, dtype=torch.int64, device="cuda")
+        mode = int(rng.integers(0, 3))
+        T.cache_tune(c, partitioned_gather=mode)
+        out = torch.full((n, dim), 5.0, dtype=host.dtype, device="cuda")
+        if call % 2:
+            T.cache_lookup_static(c, ids, out, hit_miss=hm)
+        else:
+            T.cache_lookup(c, ids, out=out, hit_miss=hm)
+        torch.cuda.synchronize()
+        assert out.cpu().numpy().tobytes() == want, (call, mode, n)
+        assert tuple(hm.tolist()) == oracle.cache_hits(res, rows, ids_np)
+        oracle.cache_count(ids_np, rows, Q)
+        assert np.array_equal(T.cache_access_counts(c).cpu().numpy().astype(np.uint32), Q)
+        if call == 1:
+            T.cache_epoch_end(c, min_overlap=cap)                    # replaces the content by the most requested rows
+            res = T.cache_residents(c).numpy()
+            Q[:] = 0
+    T.cache_free(c)
+
+
 def test_cache_rejects_unpinned_and_bad_residents():
     host = torch.zeros((100, 8), dtype=torch.float32)
     with pytest.raises(T.TaserError) as e:
