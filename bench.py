@@ -414,6 +414,7 @@ def main():
             "on the side stream")
         step_hbm_bytes += node_hbm + n_ids * 8
     step_hbm_frac = step_hbm_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS
+    gather_hbm_gbps = (edge_hbm + node_hbm) / (ms_per_step * 1e-3) / 1e9
 
     # ------------------------------------------------------------------ cache maintenance (outside the timed region)
     # Cost of the access counters of Alg. 3 inside the classify kernel, and of one epoch-end
@@ -548,11 +549,13 @@ def main():
                    "launch": launch},
         "sampler_neighbors_per_s": round(neighbors / args.steps / (sum(ms for n, (c, ms) in kernels.items()
                                                                        if n.startswith("sample_")) / args.steps * 1e-3), 1),
-        "gather_GBps": round(gather_gbps, 1), "gather_frac_of_hbm_peak": round(gather_gbps / HBM_PEAK_GBPS, 4),
-        "gather_bytes_per_step": gather_bytes_per_step,
-        "gather_note": "gather_* count algorithmic bytes (every served row read + written + id) over the whole step time; "
-                       "step_hbm_* count what must cross HBM at least once (outputs, ids, distinct source rows, sampler "
-                       "traffic) over the same time: that one is a fraction of the roofline",
+        "gather_GBps": round(gather_gbps, 1), "gather_bytes_per_step": gather_bytes_per_step,
+        "gather_hbm_GBps": round(gather_hbm_gbps, 1), "gather_hbm_frac_of_peak": round(gather_hbm_gbps / HBM_PEAK_GBPS, 4),
+        "gather_hbm_bytes_per_step": int(edge_hbm + node_hbm),
+        "gather_note": "gather_GBps counts algorithmic bytes (every served row read + written + id) over the whole step time: "
+                       "repeated rows are served by L2, so it is no fraction of the HBM peak. gather_hbm_* count what the two "
+                       "gathers must move through HBM at least once (outputs, ids, distinct source rows) over the same time, "
+                       "step_hbm_* the same plus the sampler's traffic: those are fractions of the roofline",
         "step_hbm_bytes": int(step_hbm_bytes), "step_hbm_frac": round(step_hbm_frac, 4),
         "neighbors_per_step": neighbors / args.steps,
         "cache_hit_rate": None if cache is None or sum(hm) == 0 else round(hm[0] / sum(hm), 4),
