@@ -288,10 +288,11 @@ struct RowCopy {
 // The rows of one wavefront's roots form one contiguous, 16-byte aligned range of the
 // output: `rows_here` rows whose edge ids the wave has just left in `wave_eid` (LDS, slot
 // order). The range is copied as a flat stream, 16 bytes per lane and 1 KiB per wave
-// instruction, four of them in flight; a lane finds the row of its first chunk by one
+// instruction, kInFlight of them in flight; a lane finds the row of its first chunk by one
 // division and of the following ones by stepping. A chunk inside one row is one 16-byte
 // load (4-byte aligned); one that crosses a row end takes two. Padding slots and ids
 // outside the table give zero rows.
+template <int kInFlight>
 __device__ __forceinline__ void copy_wave_rows(const RowCopy& rc, const int32_t* wave_eid, uint32_t rows_here,
                                                int64_t first_row, int lane) {
     using namespace taser_gather;
@@ -300,7 +301,6 @@ __device__ __forceinline__ void copy_wave_rows(const RowCopy& rc, const int32_t*
     uint32_t o = (uint32_t)lane * 16u;
     uint32_t row = __umulhi(o, rc.magic);
     uint32_t off = o - row * rc.row_bytes;
-    constexpr int kInFlight = 4;
     for (uint32_t base = 0; base < bytes_here; base += kInFlight * 1024u) {
         uint32_t c_o[kInFlight], c_row[kInFlight], c_off[kInFlight];
         bool whole[kInFlight], cross[kInFlight];
@@ -427,7 +427,9 @@ __global__ __launch_bounds__(kThreads) void sample_hop_kernel(
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         int64_t roots_here = num_roots - wave_q0;
         if (roots_here > kGroups) roots_here = kGroups;
-        if (roots_here > 0) copy_wave_rows(rows, eid_of_row[wave], (uint32_t)roots_here * (uint32_t)k, wave_q0 * k, lane);
+        // wave instructions of the copy in flight: four where a wavefront has four roots' rows to move, two (and
+        // 28 registers fewer) where it has one or two roots
+        if (roots_here > 0) copy_wave_rows<(G == 16 ? 4 : 2)>(rows, eid_of_row[wave], (uint32_t)roots_here * (uint32_t)k, wave_q0 * k, lane);
     }
 }
 
@@ -726,7 +728,7 @@ int check_sampling_arguments(const char* what, const taser_tcsr* g, const int32_
 // of a launch search at the same time and then copy at the same time, so the two phases add up
 // instead of overlapping, and for long rows the plain gather (one launch for all hops) moves
 // the same bytes faster. Measured on 2 x 10 slots per root: up to 8 KiB per wavefront the hop
-// kernel's own copy is as fast or faster (64-byte rows: 44 against 50 us per batch of 4 000
+// kernel's own copy is as fast or faster (64-byte rows: 41 against 49 us per batch of 4 000
 // roots, 25 against 29 us with 16 lanes per root), beyond it up to 15 % slower.
 constexpr int64_t kFinderCopyMaxWaveBytes = 8192;
 
