@@ -49,6 +49,7 @@ def main():
     ap.add_argument("--edges", type=int, default=None, help="override the event count (smaller = not the named workload)")
     ap.add_argument("--schedule", default="pipeline_node_first",
                     choices=["serial", "overlap", "pipeline", "pipeline_node_first"])
+    ap.add_argument("--lanes", type=int, default=2, help="streams that whole batches alternate between (workloads without a node cache)")
     ap.add_argument("--stage-blocks", type=int, default=32, help="width of the PCIe staging copy when it runs beside other kernels")
     ap.add_argument("--policy", default=None, choices=["recent", "uniform", "weighted", "inverse_timespan"],
                     help="override the workload's selection policy (then it is not the named workload)")
@@ -152,7 +153,7 @@ def main():
         batches.append(dict(roots=ids[:R], times=torch.from_numpy(times).to(dev), ids=ids, eids=eids, out=out))
     # Two sets of output buffers (and two cache handles, i.e. two sets of lookup scratch over
     # the same resident rows) so that consecutive batches can be in flight together.
-    n_buf = 2
+    n_buf = 2 if w.node_feat is not None else max(2, args.lanes)
     edge_out = [torch.empty((sum(n_slots), w.edge_dim), dtype=edge_dtype, device=dev) for _ in range(n_buf)]
     node_out = [None if cache is None else torch.empty((n_ids, w.node_feat.shape[1]), dtype=torch.float32, device=dev)
                 for _ in range(n_buf)]
@@ -201,16 +202,22 @@ def main():
             at += n_slots[h]
         edge_rows.append(views)
 
-    def sample(b, s):
+    def sample(b, s, stream=None):
+        stream = main if stream is None else stream
         if rows_call:
             T.sample_temporal_rows(g, b["roots"], b["times"], k, hops, policy, 42, edge_table, m=w.m, edge_weight=weight,
-                                   out=b["out"], rows_out=edge_rows[s], stream=main)
+                                   out=b["out"], rows_out=edge_rows[s], stream=stream)
         else:
-            T.sample_temporal(g, b["roots"], b["times"], k, hops, policy, 42, w.m, weight, out=b["out"], stream=main)
+            T.sample_temporal(g, b["roots"], b["times"], k, hops, policy, 42, w.m, weight, out=b["out"], stream=stream)
 
-    def edge_gather(b, s):
+    def edge_gather(b, s, stream=None):
         if not rows_call:
-            T.gather_features(edge_table, b["eids"], out=edge_out[s], stream=main)
+            T.gather_features(edge_table, b["eids"], out=edge_out[s], stream=main if stream is None else stream)
+
+    # (not for batches so small that a step is a few microseconds: there the fork and join cost more than they hide)
+    two_lanes = cache is None and args.schedule != "serial" and sum(n_slots) >= 100_000
+    lanes = [None, side] + [torch.cuda.Stream() for _ in range(n_buf - 2)]     # lane 0 is whatever `main` is at the time
+    ev_fork, ev_join = torch.cuda.Event(), [torch.cuda.Event() for _ in range(n_buf - 1)]
 
     def run(first, count):
         """`count` passes of the whole path over consecutive batches.
@@ -220,7 +227,25 @@ def main():
         pipeline: the staging of batch i also runs beside the sampling and edge gather of batch
                   i+1; the node gather of batch i is issued one batch late (two buffer sets).
         pipeline_node_first (default): the same, with the late node gather issued before the
-                  edge gather of the current batch."""
+                  edge gather of the current batch.
+        Workloads without a node cache have no bus-bound part to hide; for them every schedule but
+        `serial` lets whole batches alternate between two streams (each with its own output buffers;
+        a batch always goes to the same stream), so that the latency-bound sampling of one batch
+        runs beside the bandwidth-bound row copies of the other."""
+        if two_lanes:
+            ev_fork.record(main)
+            for x in lanes[1:]:
+                x.wait_event(ev_fork)
+            for i in range(count):
+                bi = (first + i) % len(batches)
+                s = bi % n_buf
+                lane = main if s == 0 else lanes[s]
+                sample(batches[bi], s, lane)
+                edge_gather(batches[bi], s, lane)
+            for x, e in zip(lanes[1:], ev_join):
+                e.record(x)
+                main.wait_event(e)
+            return
         pending = None
         for i in range(count):
             b, s = batches[(first + i) % len(batches)], i % n_buf
@@ -543,7 +568,8 @@ def main():
                    "policy": ["recent", "uniform", "weighted", "inverse_timespan"][policy] + ("" if args.policy is None else " (override)"), "edge_row_bytes": edge_rb,
                    "node_row_bytes": node_rb, "distinct_batches": len(batches),
                    "cache_rows": (0 if cache is None else cache.capacity) if args.cache_ratio is None
-                   else f"{cache.capacity} (override)", "schedule": args.schedule,
+                   else f"{cache.capacity} (override)",
+                   "schedule": f"batches alternate between {n_buf} streams" if two_lanes else ("serial" if cache is None else args.schedule),
                    "edge_rows": ("taser_sample_temporal_rows: " if rows_call else "taser_sample_temporal, taser_gather_features: ")
                    + ("written by the hop kernels" if fused else "one gather launch after the last hop"),
                    "launch": launch},
