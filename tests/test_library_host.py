@@ -150,3 +150,22 @@ def test_binding_fails_loudly_when_the_library_is_missing(monkeypatch):
     monkeypatch.setattr(T, "LIB_PATH", os.path.join(ROOT, "does_not_exist.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         T.lib()
+
+
+def test_no_packed_vector_instructions_in_the_device_code(tmp_path):
+    """The build switches the packed fp32 forms off (they have given wrong results on this hardware);
+    a compiler-generated packed move was also seen beside a wrong result. The device code of every
+    source must hold no v_pk_ instruction at all."""
+    import glob
+    import shutil
+    import subprocess
+    from paper_2402_05396_amd import build as B
+    if not shutil.which(B.HIPCC) and not os.path.exists(B.HIPCC):
+        pytest.skip("hipcc is not available")
+    flags = [f for f in B.FLAGS if f not in ("-shared", "-fPIC")]
+    for src in sorted(glob.glob(os.path.join(B.CSRC, "*.hip"))):
+        out = tmp_path / (os.path.basename(src) + ".s")
+        subprocess.run([B.HIPCC] + flags + ["-S", "--cuda-device-only", "-o", str(out), src], check=True,
+                       stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+        bad = [l.strip() for l in open(out) if re.match(r"\s*v_pk_", l)]
+        assert not bad, f"{os.path.basename(src)}: {bad[:3]}"
