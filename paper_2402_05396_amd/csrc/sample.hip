@@ -452,26 +452,6 @@ __device__ __forceinline__ uint64_t inverse_timespan_weight(int64_t t, int64_t t
     return (uint64_t)q + (r == d - 1u ? 1u : 0u);
 }
 
-__device__ __forceinline__ uint64_t wave_sum64(uint64_t v) {
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const uint32_t lo = __shfl_xor((uint32_t)v, d, kWave);
-        const uint32_t hi = __shfl_xor((uint32_t)(v >> 32), d, kWave);
-        v += ((uint64_t)hi << 32) | lo;
-    }
-    return v;
-}
-
-__device__ __forceinline__ uint64_t wave_inclusive_scan64(uint64_t v, int lane) {
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const uint32_t lo = __shfl_up((uint32_t)v, d, kWave);
-        const uint32_t hi = __shfl_up((uint32_t)(v >> 32), d, kWave);
-        if (lane >= d) v += ((uint64_t)hi << 32) | lo;
-    }
-    return v;
-}
-
 constexpr int kTileRows = 8;                      // registers of tile sums per lane
 constexpr int kMaxTiles = kTileRows * kWave;      // tile sums per root
 constexpr int kListThreads = 256;                 // block of the finder that reads whole lists
@@ -571,21 +551,21 @@ __global__ __launch_bounds__(kListThreads) void sample_hop_inverse_timespan_kern
     if (lane < k) u = draw64(seed_lo, seed_hi, hop, (uint64_t)q, (uint32_t)lane);
     int64_t my_pick = 0;
     for (int j = 0; j < k; ++j) {
-        uint64_t x = __umul64hi(group_get64<kWave>(u, j), total);
+        uint64_t x = __umul64hi(wave_get64(u, j), total);
         // the tile whose running sum first exceeds x
         uint64_t before = 0;
         int tile = -1;
 #pragma unroll
         for (int i = 0; i < kTileRows; ++i) {
             if (i < tile_rows && tile < 0) {
-                const uint64_t inc = wave_inclusive_scan64(tile_sum[i], lane);
+                const uint64_t inc = wave_inclusive_scan64(tile_sum[i]);
                 const uint64_t hit = __ballot(before + inc > x);
                 if (hit) {
                     const int first = __ffsll((long long)hit) - 1;
-                    x -= before + group_get64<kWave>(inc - tile_sum[i], first);
+                    x -= before + wave_get64(inc - tile_sum[i], first);
                     tile = i * kWave + first;
                 } else {
-                    before += group_get64<kWave>(inc, kWave - 1);
+                    before += wave_get64(inc, kWave - 1);
                 }
             }
         }
@@ -601,17 +581,17 @@ __global__ __launch_bounds__(kListThreads) void sample_hop_inverse_timespan_kern
             uint64_t w = 0;
             if (p < cnt) w = inverse_timespan_weight(t, ts_only[lo + p]);
             for (int e = 0; e < j; ++e) {
-                const uint64_t taken = group_get64<kWave>((uint64_t)my_pick, e);
+                const uint64_t taken = wave_get64((uint64_t)my_pick, e);
                 if ((uint64_t)p == taken) w = 0;
             }
-            const uint64_t inc = wave_inclusive_scan64(w, lane);
+            const uint64_t inc = wave_inclusive_scan64(w);
             const uint64_t hit = __ballot(before + inc > x);
             if (hit) {
                 const int first = __ffsll((long long)hit) - 1;
                 pick = r * kWave + first;
-                pick_w = group_get64<kWave>(w, first);
+                pick_w = wave_get64(w, first);
             } else {
-                before += group_get64<kWave>(inc, kWave - 1);
+                before += wave_get64(inc, kWave - 1);
             }
         }
         if (pick < 0) pick = cnt - 1;     // same remark

@@ -51,16 +51,39 @@ template <int G> __device__ __forceinline__ uint64_t group_get64(uint64_t v, int
     return ((uint64_t)group_get<G>((uint32_t)(v >> 32), sub_lane) << 32) | group_get<G>((uint32_t)v, sub_lane);
 }
 
-// Inclusive prefix sum of one 64-bit value per lane inside a group.
-template <int G> __device__ __forceinline__ uint64_t group_inclusive_scan64(uint64_t v, int sub) {
-#pragma unroll
-    for (int d = 1; d < G; d <<= 1) {
-        const uint32_t lo32 = __shfl_up((uint32_t)v, d, G);
-        const uint32_t hi32 = __shfl_up((uint32_t)(v >> 32), d, G);
-        if (sub >= d) v += ((uint64_t)hi32 << 32) | lo32;
-    }
+// The 64-bit value of the lane a DPP control points at, 0 where there is no such lane or the
+// row is masked out: one cross-lane move per half, a few cycles each, no trip through LDS.
+// CTRL: 0x110 + n = the lane n places below inside a row of 16 lanes; 0x142 / 0x143 = lane 15 of
+// the row below / lane 31, broadcast to a whole row. Every lane of the wave must be active.
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ uint64_t dpp_take64(uint64_t v) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, CTRL, ROW_MASK, 0xf, false);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(v >> 32), CTRL, ROW_MASK, 0xf, false);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// Inclusive prefix sum of one 64-bit value per lane inside a group: four shifted additions
+// inside the rows of 16 lanes, then the rows' totals handed on (to rows 1 and 3 for groups of
+// 32, and to the upper half for the whole wave). Every lane of the wave must call it.
+template <int G> __device__ __forceinline__ uint64_t group_inclusive_scan64(uint64_t v, int /*sub*/) {
+    v += dpp_take64<0x111, 0xf>(v);
+    v += dpp_take64<0x112, 0xf>(v);
+    v += dpp_take64<0x114, 0xf>(v);
+    v += dpp_take64<0x118, 0xf>(v);
+    if (G >= 32) v += dpp_take64<0x142, 0xa>(v);
+    if (G == 64) v += dpp_take64<0x143, 0xc>(v);
     return v;
 }
+
+// The 64-bit value of one lane of the wave; `lane` must be the same in every lane.
+__device__ __forceinline__ uint64_t wave_get64(uint64_t v, int lane) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, lane);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), lane);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// Inclusive prefix sum over the whole wave, and the wave's total in every lane.
+__device__ __forceinline__ uint64_t wave_inclusive_scan64(uint64_t v) { return group_inclusive_scan64<64>(v, 0); }
+__device__ __forceinline__ uint64_t wave_sum64(uint64_t v) { return wave_get64(wave_inclusive_scan64(v), 63); }
 
 // One of k successive weighted draws without replacement inside a group whose lane i
 // holds candidate i: `run` is the inclusive prefix sum of the weights still in play,

@@ -29,31 +29,6 @@ constexpr int kThreads = 256;
 constexpr int kFan = 1024;             // values per partial sum
 constexpr uint32_t kDrawTag = 0x4253454Cu;
 
-__device__ __forceinline__ uint64_t wave_sum(uint64_t v) {
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const uint32_t lo = __shfl_xor((uint32_t)v, d, kWave);
-        const uint32_t hi = __shfl_xor((uint32_t)(v >> 32), d, kWave);
-        v += ((uint64_t)hi << 32) | lo;
-    }
-    return v;
-}
-
-__device__ __forceinline__ uint64_t wave_inclusive_scan(uint64_t v, int lane) {
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const uint32_t lo = __shfl_up((uint32_t)v, d, kWave);
-        const uint32_t hi = __shfl_up((uint32_t)(v >> 32), d, kWave);
-        if (lane >= d) v += ((uint64_t)hi << 32) | lo;
-    }
-    return v;
-}
-
-__device__ __forceinline__ uint64_t wave_get64(uint64_t v, int lane) {
-    return ((uint64_t)(uint32_t)__shfl((int)(uint32_t)(v >> 32), lane, kWave) << 32) |
-           (uint32_t)__shfl((int)(uint32_t)v, lane, kWave);
-}
-
 // First index i in [begin, end) whose running sum over a[begin..i] exceeds x, by
 // one wavefront, 64 values per step; x is reduced by the sum before a[i]. The
 // caller guarantees that the whole range sums to more than x. Wave-uniform.
@@ -65,7 +40,7 @@ __device__ __forceinline__ int64_t wave_descend(const T* __restrict__ a, int64_t
     for (int64_t row = begin; row < end; row += kWave) {
         const int64_t i = row + lane;
         const uint64_t v = i < end ? (uint64_t)a[i] : 0;
-        const uint64_t inc = wave_inclusive_scan(v, lane);
+        const uint64_t inc = wave_inclusive_scan64(v);
         const uint64_t hit = __ballot(before + inc > x);
         if (hit) {
             const int first = __ffsll((long long)hit) - 1;
@@ -102,7 +77,7 @@ __device__ __forceinline__ int64_t wave_descend_group(const T* __restrict__ a, i
     uint64_t own = 0;
 #pragma unroll
     for (int i = 0; i < kPer; ++i) own += (uint64_t)v[i];
-    const uint64_t inc = wave_inclusive_scan(own, lane);
+    const uint64_t inc = wave_inclusive_scan64(own);
     const uint64_t hit = __ballot(inc > x);
     const int first = hit ? __ffsll((long long)hit) - 1 : kWave - 1;   // hit is never 0 while the guarantee holds
     uint64_t rest = x - wave_get64(inc - own, first);                  // what is left inside that lane
@@ -134,7 +109,7 @@ __global__ __launch_bounds__(kThreads) void partial_sums_kernel(const T* __restr
     uint64_t s = 0;
     for (int j = threadIdx.x; j < kFan; j += kThreads)
         if (base + j < n) s += (uint64_t)in[base + j];
-    s = wave_sum(s);
+    s = wave_sum64(s);
     if ((threadIdx.x & (kWave - 1)) == 0) part[threadIdx.x >> 6] = s;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -159,7 +134,7 @@ __global__ __launch_bounds__(kThreads) void batch_draw_kernel(const uint32_t* __
     if (j >= b) return;   // wave-uniform
     uint64_t total = 0;
     for (int64_t i = lane; i < n2; i += kWave) total += sum2[i];
-    total = wave_sum(total);
+    total = wave_sum64(total);
     if (total == 0) {
         if (lane == 0) out[j] = -1;
         return;
@@ -210,7 +185,7 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const int32_t* __restri
     const int leader = __ffsll((long long)changing) - 1;
     const int32_t top = diff ? e / (kFan * kFan) : -1;
     const int32_t leader_top = __shfl(top, leader, kWave);
-    const uint64_t together = wave_sum(top == leader_top ? diff : 0);
+    const uint64_t together = wave_sum64(top == leader_top ? diff : 0);
     if (lane == leader) {
         if (together) atomicAdd((unsigned long long*)&sum2[leader_top], (unsigned long long)together);
     } else if (diff && top != leader_top) {
