@@ -169,3 +169,12 @@ def test_no_packed_vector_instructions_in_the_device_code(tmp_path):
                        stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
         bad = [l.strip() for l in open(out) if re.match(r"\s*v_pk_", l)]
         assert not bad, f"{os.path.basename(src)}: {bad[:3]}"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Nothing in this build uses a second GPU: bench.py says so instead of running."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
