@@ -904,6 +904,41 @@ def test_whole_step_replays_from_a_hip_graph():
         assert tuple(hit_miss.tolist()) == oracle.cache_hits(T.cache_residents(cache).numpy(), w.num_nodes, ids)
 
 
+def test_finder_with_rows_replays_from_a_hip_graph():
+    """taser_sample_temporal_rows (hop kernels writing the rows: C1 has 64-byte edge rows) captured
+    into a HIP graph and replayed with new roots in the same buffers; every replay equals the oracle."""
+    w = W.make(1)
+    g, g_ref = build_both(w.src, w.dst, w.ts, w.eid, w.num_nodes)
+    table = dev(w.edge_feat)
+    R, k = 600, 10
+    roots_d = torch.empty(R, dtype=torch.int32, device="cuda")
+    times_d = torch.empty(R, dtype=torch.int64, device="cuda")
+    roots, times = w.batches[2]
+    roots_d.copy_(torch.from_numpy(roots))
+    times_d.copy_(torch.from_numpy(times))
+    out, rows = T.sample_temporal_rows(g, roots_d, times_d, k, 2, T.UNIFORM, 77, table)      # warm-up and buffers
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            T.sample_temporal_rows(g, roots_d, times_d, k, 2, T.UNIFORM, 77, table, out=out, rows_out=rows)
+    torch.cuda.current_stream().wait_stream(side)
+    for b in (8, 0, 5):
+        roots, times = w.batches[b]
+        roots_d.copy_(torch.from_numpy(roots))                        # eager work between the replays
+        times_d.copy_(torch.from_numpy(times))
+        for r in rows:
+            r.fill_(9.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        want = oracle.sample_temporal(g_ref, roots, times, k, 2, W.UNIFORM, 77, threads=THREADS)
+        assert_hops_equal(out, want)
+        for h in range(2):
+            assert rows[h].cpu().numpy().tobytes() == oracle.gather(w.edge_feat, want[h]["eid"].ravel()).tobytes()
+
+
 def test_two_stream_step_replays_from_a_hip_graph():
     """The same step with the lookup split over two streams, as the benchmark's pipelined schedule
     issues it: the classification and the staging of missed rows on a side stream that is forked
