@@ -50,7 +50,7 @@ def main():
     ap.add_argument("--schedule", default="pipeline_node_first",
                     choices=["serial", "overlap", "pipeline", "pipeline_node_first"])
     ap.add_argument("--lanes", type=int, default=2, help="streams that whole batches alternate between (workloads without a node cache)")
-    ap.add_argument("--stage-blocks", type=int, default=32, help="width of the PCIe staging copy when it runs beside other kernels")
+    ap.add_argument("--stage-blocks", type=int, default=24, help="width of the PCIe staging copy when it runs beside other kernels")
     ap.add_argument("--policy", default=None, choices=["recent", "uniform", "weighted", "inverse_timespan"],
                     help="override the workload's selection policy (then it is not the named workload)")
     ap.add_argument("--launch", default="graph", choices=["graph", "eager"],
