@@ -904,6 +904,35 @@ def test_whole_step_replays_from_a_hip_graph():
         assert tuple(hit_miss.tolist()) == oracle.cache_hits(T.cache_residents(cache).numpy(), w.num_nodes, ids)
 
 
+def test_sampling_with_rows_into_one_buffer_for_all_hops():
+    """Edge ids and rows of all hops as consecutive views of one buffer each (the benchmark's layout):
+    for rows too long for the hop kernels the call then launches one gather for all hops."""
+    w = W.make(3, num_batches=1)
+    g, g_ref = build_both(w.src, w.dst, w.ts, w.eid, w.num_nodes)
+    table = dev(w.edge_feat)
+    roots, times = w.batches[0]
+    roots, times = roots[:1501], times[:1501]
+    k, hops, d = w.k, 3, w.edge_feat.shape[1]
+    n_slots = [roots.shape[0] * k ** (h + 1) for h in range(hops)]
+    eids = torch.full((sum(n_slots),), -7, dtype=torch.int32, device="cuda")
+    rows = torch.full((sum(n_slots) + 3, d), 5.0, dtype=table.dtype, device="cuda")
+    out, views, at, r = [], [], 0, roots.shape[0]
+    for h in range(hops):
+        out.append(dict(nbr=torch.empty(n_slots[h], dtype=torch.int32, device="cuda"), eid=eids[at:at + n_slots[h]],
+                        ts=torch.empty(n_slots[h], dtype=torch.int64, device="cuda"), count=torch.empty(r, dtype=torch.int32, device="cuda")))
+        views.append(rows[at:at + n_slots[h]])
+        at += n_slots[h]
+        r *= k
+    T.sample_temporal_rows(g, dev(roots), dev(times), k, hops, T.UNIFORM, 11, table, out=out, rows_out=views)
+    torch.cuda.synchronize()
+    want = oracle.sample_temporal(g_ref, roots, times, k, hops, W.UNIFORM, 11, threads=THREADS)
+    all_eids = np.concatenate([o["eid"].ravel() for o in want])
+    assert np.array_equal(eids.cpu().numpy(), all_eids)
+    got = rows.cpu().numpy()
+    assert got[:sum(n_slots)].tobytes() == oracle.gather(w.edge_feat, all_eids, threads=THREADS).tobytes()
+    assert (got[sum(n_slots):] == 5.0).all()
+
+
 def test_finder_with_rows_replays_from_a_hip_graph():
     """taser_sample_temporal_rows (hop kernels writing the rows: C1 has 64-byte edge rows) captured
     into a HIP graph and replayed with new roots in the same buffers; every replay equals the oracle."""
