@@ -515,8 +515,9 @@ def main():
         node_ref = None
         if w.node_feat is not None:
             node_ref = oracle.gather(w.node_feat, np.concatenate([roots[:nr]] + [o["nbr"].ravel() for o in ref]), threads=threads)
+        edge_ref = None
         if w.edge_feat is not None:
-            oracle.gather(w.edge_feat, np.concatenate([o["eid"].ravel() for o in ref]), threads=threads)
+            edge_ref = oracle.gather(w.edge_feat, np.concatenate([o["eid"].ravel() for o in ref]), threads=threads)
         t_gather = time.perf_counter() - t0
         cpu_neighbors = sum(int(o["count"].sum()) for o in ref)
         # the oracle must agree with what the device produced for the same roots
@@ -527,6 +528,13 @@ def main():
             for f in ("nbr", "eid", "ts"):
                 assert np.array_equal(got[h][f][:nr * k ** (h + 1)].cpu().numpy(), ref[h][f].ravel()), f"GPU/oracle mismatch: hop {h} {f}"
             assert np.array_equal(got[h]["count"][:nr * k ** h].cpu().numpy(), ref[h]["count"].ravel()), f"GPU/oracle mismatch: hop {h} count"
+        if edge_ref is not None:
+            # the edge rows of those roots' slots (run(0, 1) left them in edge_out[0], hop after hop)
+            at, parts = 0, []
+            for h in range(hops):
+                parts.append(edge_out[0][at:at + nr * k ** (h + 1)])
+                at += n_slots[h]
+            assert torch.cat(parts).cpu().numpy().tobytes() == edge_ref.tobytes(), "GPU/oracle mismatch: edge rows"
         if node_ref is not None:
             # the node rows the device served for those roots and their sampled neighbors (run(0, 1) left them in node_out[0])
             at, parts, r_h = 0, [node_out[0][:nr]], R
